@@ -1,0 +1,199 @@
+/*
+ * dfsattn.h - C ABI of the DFSAttn attention path for AMD MI355X (gfx950).
+ *
+ * The library runs the sparse 3D self-attention of a video diffusion transformer as the
+ * paper's Algorithm 1 states it: a 3D Hilbert-curve token reorder, hierarchical block
+ * scoring, top-k / adaptive block-mask selection, block-sparse attention over the
+ * reordered sequence, and the inverse reorder.
+ *
+ * Conventions shared by every entry point
+ *   - `g` points to HOST memory.  Every other pointer is DEVICE memory owned by the caller;
+ *     the library allocates nothing, frees nothing and keeps no pointer after a call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no call synchronises or copies to the host.
+ *   - Tensors are dense row-major.  Q, K, V, O are [heads, tokens, d]; a batch dimension
+ *     folds into `heads`.  Source ("raster") order has N = T*H*W + n_text tokens, video token
+ *     n = (t*H + h)*W + w (Sec. 3.1), text tokens after them.  Reordered tensors have
+ *     N_pad = M*B rows: the M_v = ceil(T*H*W/B) video blocks in Hilbert order, zero-padded
+ *     at the tail of the last one (Sec. 3.2), then the M_x = ceil(n_text/B) text blocks.
+ *   - Return value: DFS_OK or a negative dfs_status.  Arguments are checked on the host
+ *     before anything is launched; after an error dfs_last_error() describes it.  A scratch
+ *     buffer `ws` must hold at least dfs_workspace_bytes() bytes and be 256-byte aligned;
+ *     its contents are undefined afterwards.
+ */
+#ifndef DFSATTN_H
+#define DFSATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DFS_OK = 0,
+  DFS_EINVAL = -1,     /* null pointer, bad enum, bad ratio */
+  DFS_ESHAPE = -2,     /* geometry outside what the kernels support */
+  DFS_EDTYPE = -3,     /* dtype not supported by this entry point */
+  DFS_EWORKSPACE = -4, /* ws missing, misaligned or too small */
+  DFS_EHIP = -5        /* a HIP call failed; dfs_last_error() holds its message */
+} dfs_status;
+
+typedef enum { DFS_F32 = 0, DFS_BF16 = 1 } dfs_dtype;
+
+typedef enum {
+  DFS_SELECT_TOPK = 0,     /* Eq. 9: every query block keeps ceil((1-sparsity)*M_v) key blocks */
+  DFS_SELECT_MASS_HEAD = 1 /* per-head keep count from the cumulative score mass (see dfs_select_mask) */
+} dfs_select_mode;
+
+/* Problem geometry (Algorithm 1 inputs; Sec. 3.1 for the token layout). */
+typedef struct {
+  int32_t T, H, W;   /* latent grid: frames, height, width; each in [1, 512] */
+  int32_t n_text;    /* appended tokens that always stay dense (Fig. 1), 0 if none */
+  int32_t heads;     /* number of (batch x head) slices */
+  int32_t d;         /* head dimension: 64 or 128 */
+  int32_t B;         /* block size: 64 or 128 (Sec. 6.1 uses 128) */
+  int32_t Bs;        /* sub-block size: divides B, B/Bs in {1,2,4,8} (Table 4) */
+} dfs_geom;
+
+/* Sizes that follow from a geometry. */
+typedef struct {
+  int64_t N_v;    /* T*H*W video tokens */
+  int64_t N;      /* N_v + n_text */
+  int64_t N_pad;  /* M*B rows of every reordered tensor */
+  int32_t M_v;    /* video blocks */
+  int32_t M_x;    /* text blocks */
+  int32_t M;      /* M_v + M_x */
+  int32_t r;      /* sub-blocks per block, B/Bs */
+  int32_t M_s;    /* video sub-blocks, M_v*r */
+  int32_t bits;   /* bits per axis of the enclosing power-of-two cube */
+} dfs_sizes;
+
+typedef enum {
+  DFS_WS_HILBERT_PERM = 0,
+  DFS_WS_BLOCK_SCORE = 1,
+  DFS_WS_SELECT_MASK = 2,
+  DFS_WS_FORWARD = 3,      /* dfs_forward on fp32 tensors */
+  DFS_WS_FORWARD_BF16 = 4  /* dfs_forward on bf16 tensors */
+} dfs_ws_kind;
+
+/* Validates `g` and fills `out`.  Host only. */
+int dfs_geom_sizes(const dfs_geom* g, dfs_sizes* out);
+
+/* Bytes of scratch the given entry point needs for `g` (0 if the geometry is invalid). Host only. */
+size_t dfs_workspace_bytes(const dfs_geom* g, int kind);
+
+/* Message of the calling thread's most recent failed call; never NULL. */
+const char* dfs_last_error(void);
+
+/* Keep count of DFS_SELECT_TOPK: clamp(ceil((1-sparsity)*M_v - 1e-6), 1, M_v) in double (Eq. 9,
+ * with the rounding the paper leaves open).  Host only; returns 0 on invalid arguments. */
+int32_t dfs_keep_count(double sparsity, int32_t M_v);
+
+/*
+ * Token permutation P (Sec. 5.1; Algorithm 1 step 1).  Video tokens are ordered by the 3D
+ * Hilbert index of their cell (t,h,w) in the smallest power-of-two cube holding the grid
+ * (Butz curve in Skilling's transpose form, t the most significant axis of each octal digit);
+ * text tokens keep their order behind the video blocks.
+ *   perm_pad  [N_pad] out  source token of each reordered position, -1 on pad positions
+ *   inv       [N]     out  reordered position of each source token
+ *   blk_valid [M]     out  real tokens per block (pads are always at a block's tail)
+ * Computed once per geometry ("static index mapping", Sec. 6.3).  ws: DFS_WS_HILBERT_PERM.
+ */
+int dfs_hilbert_perm(const dfs_geom* g, int32_t* perm_pad, int32_t* inv, int32_t* blk_valid,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * X' = P(X) (Algorithm 1 step 1): x_perm[h, p, :] = x[h, perm_pad[p], :], zeros where
+ * perm_pad[p] < 0.   x [heads, N, d] in, x_perm [heads, N_pad, d] out, both of `dtype`.
+ */
+int dfs_permute(const dfs_geom* g, int dtype, const void* x, const int32_t* perm_pad,
+                void* x_perm, void* stream);
+
+/*
+ * Hierarchical block score (Sec. 5.2; Algorithm 1 step 2; Eq. 2 and Eq. 8).  Q' and K' are
+ * average-pooled over sub-blocks of Bs rows (mean over real rows; a sub-block without real
+ * rows is empty), A_hat = row-softmax(Q_hat K_hat^T / sqrt(d)) over the non-empty video
+ * sub-blocks, and score[h,u,v] = sum of the r x r entries of A_hat in block pair (u,v).
+ * Text blocks are not scored.  Arithmetic is fp32.
+ *   q_perm, k_perm [heads, N_pad, d] in (`dtype`);  score [heads, M_v, M_v] out, fp32.
+ * ws: DFS_WS_BLOCK_SCORE.
+ */
+int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
+                    float* score, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block-mask selection (Eq. 9).  Per (head, query block u) the key blocks are ranked by score,
+ * higher first, equal scores by lower index, and the first k are kept.
+ *   DFS_SELECT_TOPK:      k = dfs_keep_count(sparsity, M_v) for every head.
+ *   DFS_SELECT_MASS_HEAD: per row, k_u = the fewest top blocks whose scores hold a fraction
+ *     `mass` of the row total, with scores taken to fixed point floor(clamp(s,0,4096)*2^24) so
+ *     that the sums are exact, target ceil(mass*total) in double, k_u >= 1; per head
+ *     k_h = max(ceil(mean_u k_u), dfs_keep_count(sparsity, M_v)) with `sparsity` the cap; k_h is
+ *     clamped to K_max - M_x.  (This rule is the benchmark's adaptive ratio, not the step
+ *     schedule of Sec. 5.3, which is a host policy on `sparsity`.)
+ * Text: video query blocks also keep all M_x text key blocks; text query blocks keep all M.
+ *   score  [heads, M_v, M_v] in
+ *   mask   [heads, M, M] out, uint8 0/1, may be NULL
+ *   kv_idx [heads, M, K_max] out: kept key blocks of each query block, ascending; entries at or
+ *          beyond the count are unspecified; rows that keep all M blocks are not written
+ *   kv_cnt [heads, M] out: number of kept key blocks
+ *   k_head [heads] out, may be NULL: the k used for each head
+ *   K_max >= k + M_x (TOPK), >= dfs_keep_count(cap) + M_x (MASS_HEAD)
+ * ws: DFS_WS_SELECT_MASK.
+ */
+int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double sparsity, double mass,
+                    uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max, int32_t* k_head,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Block-sparse attention forward over the reordered sequence (Algorithm 1 step 3; Eq. 1 on the
+ * kept block pairs).  For a real query position p in block u, the keys are the real positions of
+ * the blocks kv_idx[h,u,0..kv_cnt[h,u]) and o_perm[h,p,:] = sum_j softmax_j(scale <q_p,k_j>) v_j
+ * with the softmax normalised over those keys.  A query block with kv_cnt == M attends to every
+ * block and its kv_idx row is not read; with kv_cnt == 0 its output rows are zero.
+ * bf16: products on the matrix cores, fp32 accumulation and softmax, output rounded to bf16.
+ * f32:  fp32 throughout.
+ *   q_perm, k_perm, v_perm [heads, N_pad, d] in;  o_perm [heads, N_pad, d] out (pad rows unspecified)
+ *   lse [heads, N_pad] out or NULL: natural-log sum of exp(scale*logit) over the kept keys
+ *   scale: softmax scale, 1/sqrt(d) in the paper.
+ */
+int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
+                        const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max,
+                        float scale, void* o_perm, float* lse, void* stream);
+
+/*
+ * O = P^{-1}(O') (Algorithm 1 step 3, last line): o[h, n, :] = o_perm[h, inv[n], :].
+ *   o_perm [heads, N_pad, d] in, o [heads, N, d] out.
+ */
+int dfs_unperm(const dfs_geom* g, int dtype, const void* o_perm, const int32_t* inv, void* o, void* stream);
+
+/*
+ * Mask state of one attention layer that survives across diffusion steps (Sec. 5.3): the caller
+ * owns the buffers and passes them to every step.
+ */
+typedef struct {
+  int32_t* kv_idx;   /* [heads, M, K_max] */
+  int32_t* kv_cnt;   /* [heads, M] */
+  uint8_t* mask;     /* [heads, M, M] or NULL */
+  int32_t* k_head;   /* [heads] or NULL */
+  int32_t K_max;
+} dfs_mask_state;
+
+/*
+ * One call of Algorithm 1 for one layer: reorder Q, K, V; if `refresh` is non-zero recompute the
+ * block mask into `st` (scoring + selection as above), otherwise reuse it (Sec. 5.3: masks are
+ * refreshed every Delta steps, outputs are recomputed every step); block-sparse attention; inverse
+ * reorder.  perm_pad / inv come from dfs_hilbert_perm.
+ *   q, k, v [heads, N, d] in;  o [heads, N, d] out.   ws: DFS_WS_FORWARD (f32) or DFS_WS_FORWARD_BF16.
+ */
+int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, const void* v,
+                const int32_t* perm_pad, const int32_t* inv, int refresh, int mode, double sparsity,
+                double mass, dfs_mask_state* st, float scale, void* o, void* ws, size_t ws_bytes,
+                void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFSATTN_H */

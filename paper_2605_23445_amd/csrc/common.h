@@ -1,0 +1,46 @@
+// Internal helpers shared by the HIP translation units of libdfsattn (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dfsattn.h"
+
+namespace dfs {
+
+// Records `msg` as the calling thread's last error and returns `code`.
+int fail(int code, const char* fmt, ...);
+// Validates a geometry (sets the error on failure) and fills the derived sizes.
+int check_geom(const dfs_geom* g, dfs_sizes* s);
+// Turns the error state left by a kernel launch into a status code.
+int launch_status(const char* what);
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+inline int elem_size(int dtype) { return dtype == DFS_BF16 ? 2 : 4; }
+
+// Stage entry points without argument checks, used by dfs_forward after it has validated once.
+int run_permute(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* x, const int32_t* perm_pad,
+                void* x_perm, hipStream_t st);
+int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm,
+                    float* score, void* ws, hipStream_t st);
+int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, int mode, double sparsity,
+                    double mass, uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max,
+                    int32_t* k_head, void* ws, hipStream_t st);
+int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q, const void* k, const void* v,
+                    const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale, void* o, float* lse,
+                    hipStream_t st);
+int run_unperm(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* o_perm, const int32_t* inv, void* o,
+               hipStream_t st);
+size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s);
+size_t ws_select_mask(const dfs_geom* g, const dfs_sizes& s);
+size_t ws_hilbert(const dfs_sizes& s);
+
+// bf16 <-> fp32 on raw bits (round to nearest even on the way down)
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+}  // namespace dfs

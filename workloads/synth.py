@@ -12,12 +12,15 @@ follows spatio-temporal proximity (Sec. 5.1):
 
 with F = 8 random frequencies omega_f ~ N(0, I/ell^2) per head, a few high-norm
 "sink" key tokens per frame, and optional appended text rows ~ N(0,1).  Everything
-is drawn on the host with numpy's counter-free PCG64 streams keyed by
+is drawn on the host with numpy PCG64 streams keyed by
 (seed, tensor id, head), so any head can be generated on its own.
 
 Nothing here computes any step of the attention method.
 """
 from __future__ import annotations
+
+import os
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -97,7 +100,7 @@ def make_head(w: Workload, head: int, pos: np.ndarray | None = None):
     return q.astype(np.float32), k.astype(np.float32), v.astype(np.float32)
 
 
-def make_qkv(w: Workload, heads=None):
+def make_qkv(w: Workload, heads=None, threads: int = 0):
     """Q, K, V as [heads, N, d] arrays in raster order.
 
     For a bf16 workload the arrays hold bf16 bit patterns (uint16); for an f32
@@ -111,12 +114,21 @@ def make_qkv(w: Workload, heads=None):
     q = np.empty((len(head_ids), N, w.d), dtype=dt)
     k = np.empty_like(q)
     v = np.empty_like(q)
-    for i, h in enumerate(head_ids):
-        qh, kh, vh = make_head(w, h, pos)
+
+    def one(i):
+        qh, kh, vh = make_head(w, head_ids[i], pos)
         if w.dtype == "bf16":
             q[i], k[i], v[i] = to_bf16_bits(qh), to_bf16_bits(kh), to_bf16_bits(vh)
         else:
             q[i], k[i], v[i] = qh, kh, vh
+
+    workers = min(len(head_ids), threads if threads else min(16, os.cpu_count() or 1))
+    if workers > 1:      # heads are independent streams; numpy releases the GIL in its kernels
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(one, range(len(head_ids))))
+    else:
+        for i in range(len(head_ids)):
+            one(i)
     return q, k, v
 
 
