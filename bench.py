@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the DFSAttn attention path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic Q, K, V (all heads of one
+attention layer): Hilbert permutation, reorder of Q/K/V, hierarchical block scoring, top-k block
+selection, block-sparse attention, inverse reorder.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload wan] [--sparsity 0.9]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan")
+    ap.add_argument("--sparsity", type=float, default=0.9)
+    ap.add_argument("--heads", type=int, default=0, help="override the head count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
+                    help="scaled rocprofv3 FETCH_SIZE / WRITE_SIZE of the attention kernel, KiB per launch")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (heads would shard across GPUs with no exchange inside the "
+              "path, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2605_23445_amd as P
+    from workloads import CONFIGS, derived_sizes, make_qkv
+
+    w = CONFIGS[a.workload]
+    if a.heads:
+        w = w.with_heads(a.heads)
+    sz = derived_sizes(w)
+    torch.cuda.set_device(0)
+    g = P.Geom(w.T, w.H, w.W, w.n_text, w.heads, w.d, w.B, w.Bs)
+    dt = P.DFS_BF16 if w.dtype == "bf16" else P.DFS_F32
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    t0 = time.time()
+    q, k, v = make_qkv(w)
+    dev = []
+    for x in (q, k, v):
+        t = torch.from_numpy(x)
+        dev.append((t.view(torch.bfloat16) if w.dtype == "bf16" else t).cuda())
+    qd, kd, vd = dev
+    gen_s = time.time() - t0
+
+    N_pad, M, M_v, M_x = sz["N_pad"], sz["M"], sz["M_v"], sz["M_x"]
+    k_keep = P.dfs_keep_count(a.sparsity, M_v)
+    K_max = k_keep + M_x
+    i32 = dict(dtype=torch.int32, device="cuda")
+    perm_pad, inv, blk_valid = torch.empty(N_pad, **i32), torch.empty(sz["N"], **i32), torch.empty(M, **i32)
+    qp, kp, vp, op = (torch.empty((w.heads, N_pad, w.d), dtype=tdt, device="cuda") for _ in range(4))
+    o = torch.empty_like(qd)
+    score = torch.empty((w.heads, M_v, M_v), dtype=torch.float32, device="cuda")
+    kv_idx, kv_cnt = torch.empty((w.heads, M, K_max), **i32), torch.empty((w.heads, M), **i32)
+    ws = torch.empty(max(P.dfs_workspace_bytes(g, kk) for kk in (P.DFS_WS_HILBERT_PERM, P.DFS_WS_BLOCK_SCORE, P.DFS_WS_SELECT_MASK)),
+                     dtype=torch.uint8, device="cuda")
+    scale = 1.0 / math.sqrt(w.d)
+
+    stages = ["perm_index", "permute_qkv", "block_score", "select_mask", "sparse_attn", "unperm"]
+    n_ev = a.steps * (len(stages) + 1)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+
+    def step(evs=None):
+        def mark(i):
+            if evs is not None:
+                evs[i].record()
+        mark(0)
+        P.dfs_hilbert_perm(g, perm_pad, inv, blk_valid, ws); mark(1)
+        P.dfs_permute(g, dt, qd, perm_pad, qp)
+        P.dfs_permute(g, dt, kd, perm_pad, kp)
+        P.dfs_permute(g, dt, vd, perm_pad, vp); mark(2)
+        P.dfs_block_score(g, dt, qp, kp, score, ws); mark(3)
+        P.dfs_select_mask(g, score, P.DFS_SELECT_TOPK, a.sparsity, 0.0, None, kv_idx, kv_cnt, K_max, None, ws); mark(4)
+        P.dfs_sparse_attn_fwd(g, dt, qp, kp, vp, kv_idx, kv_cnt, K_max, scale, op, None); mark(5)
+        P.dfs_unperm(g, dt, op, inv, o); mark(6)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(a.steps):
+        step(events[s * 7:(s + 1) * 7])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_step = wall * 1e3 / a.steps
+    stage_ms = {name: sum(events[s * 7 + i].elapsed_time(events[s * 7 + i + 1]) for s in range(a.steps)) / a.steps
+                for i, name in enumerate(stages)}
+
+    cnt = kv_cnt.cpu().numpy().astype(np.int64)
+    pairs = int(cnt.sum())
+    flop_exec = pairs * 4.0 * w.B * w.B * w.d
+    flop_dense = 4.0 * float(sz["N"]) ** 2 * w.d * w.heads
+    attn_ms = stage_ms["sparse_attn"]
+    e = 2 if w.dtype == "bf16" else 4
+    bytes_permute = 3 * w.heads * (sz["N"] + N_pad) * w.d * e + 3 * N_pad * 4
+    bytes_unperm = 2 * w.heads * sz["N"] * w.d * e + sz["N"] * 4
+    out = {
+        "metric": "dense-equivalent attention TFLOP/s of one whole DFSAttn step (reorder + block scoring + "
+                  "top-k selection + block-sparse attention + inverse reorder) at the given sparsity",
+        "value": flop_dense / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: grid {w.T}x{w.H}x{w.W} (+{w.n_text} text), {sz['N']} tokens, {w.heads} heads, "
+                               f"d={w.d}, B={w.B}, Bs={w.Bs}", "sparsity": a.sparsity, "kept_blocks_per_row": k_keep,
+                   "achieved_sparsity": 1.0 - pairs / float(w.heads * M * M), "input_gen_s": round(gen_s, 1)},
+        "attn_kernel_ms": attn_ms,
+        "attn_executed_tflops": flop_exec / (attn_ms * 1e-3) / 1e12,
+        "attn_dense_equiv_tflops": flop_dense / (attn_ms * 1e-3) / 1e12,
+        "mfma_util_pct": 100.0 * flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "stage_ms": {k2: round(v2, 4) for k2, v2 in stage_ms.items()},
+        "permute_gbs": bytes_permute / (stage_ms["permute_qkv"] * 1e-3) / 1e9,
+        "unperm_gbs": bytes_unperm / (stage_ms["unperm"] * 1e-3) / 1e9,
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
+                     "achieved": flop_exec / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "traffic": None if a.traffic_kib is None else {"fetch_bytes": a.traffic_kib[0] * 1024, "write_bytes": a.traffic_kib[1] * 1024,
+                                                                   "algorithmic_bytes": 4.0 * w.heads * N_pad * w.d * e}},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, sz, a.sparsity, q, k, v, flop_dense)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, sz, sparsity, q, k, v, flop_dense):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: permutation in full,
+    scoring + selection + attention on the first heads / seeded query blocks, extrapolated by work."""
+    import numpy as np
+    from oracle import dfs_oracle as O
+    from workloads.synth import as_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    perm_pad, inv, blk_valid = O.hilbert_perm(w.T, w.H, w.W, w.n_text, w.B)
+    t_perm = time.perf_counter() - t0
+    hs = list(range(min(3, w.heads)))
+    t0 = time.perf_counter()
+    qp, kp, vp = (O.permute(as_f64(x[hs]), perm_pad) for x in (q, k, v))
+    t_permute = (time.perf_counter() - t0) / len(hs)
+    t0 = time.perf_counter()
+    score = O.block_score(qp, kp, sz["N_v"], w.B, w.Bs).astype(np.float32)
+    mask, kk = O.select_topk(score, sparsity, sz["M_x"])
+    t_score = (time.perf_counter() - t0) / len(hs)
+    rng = np.random.default_rng(w.seed)
+    blocks = sorted(set(int(x) for x in rng.choice(sz["M_v"], size=min(240, sz["M_v"]), replace=False)))
+    t0 = time.perf_counter()
+    O.sparse_attn(qp, kp, vp, mask, blk_valid, w.B, q_blocks=blocks)
+    t_attn = time.perf_counter() - t0
+    pairs_sample = int(mask[:, blocks].sum())
+    pairs_total_head = int(mask.sum()) / len(hs)
+    est_head = t_permute * 4.0 / 3.0 + t_score + t_attn * pairs_total_head / pairs_sample
+    est_total = t_perm + est_head * w.heads
+    return {"value": flop_dense / est_total / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle (numpy fp64) on heads 0..{len(hs) - 1}: permutation, reorder, scoring and selection in full, attention on "
+                      f"{len(blocks)} seeded query blocks per head ({pairs_sample} kept block pairs of {int(pairs_total_head * w.heads)} in the step); whole-step time "
+                      f"extrapolated by kept pairs and head count: {est_total:.1f} s per step",
+            "measured_s": {"perm_index": t_perm, "reorder_head": t_permute, "score_select_head": t_score, "attn_sample": t_attn}}
+
+
+if __name__ == "__main__":
+    main()

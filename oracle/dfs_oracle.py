@@ -268,7 +268,8 @@ def select_mass_head(score: np.ndarray, mass: float, cap_sparsity: float, M_x: i
 
 
 def mask_to_lists(mask: np.ndarray, K_max: int):
-    """kv_idx [heads, M, K_max] (ascending kept columns, -1 beyond the count) and kv_cnt."""
+    """kv_idx [heads, M, K_max] (ascending kept columns, -1 beyond the count) and kv_cnt.
+    A row that keeps all M blocks needs no list; it is listed only if K_max has room for it."""
     heads, M, _ = mask.shape
     kv_idx = np.full((heads, M, K_max), -1, dtype=np.int32)
     kv_cnt = np.zeros((heads, M), dtype=np.int32)
@@ -276,7 +277,10 @@ def mask_to_lists(mask: np.ndarray, K_max: int):
         for u in range(M):
             cols = np.nonzero(mask[h, u])[0]
             kv_cnt[h, u] = cols.shape[0]
-            kv_idx[h, u, :cols.shape[0]] = cols
+            if cols.shape[0] <= K_max:
+                kv_idx[h, u, :cols.shape[0]] = cols
+            else:
+                assert cols.shape[0] == M
     return kv_idx, kv_cnt
 
 

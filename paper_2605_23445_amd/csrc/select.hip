@@ -173,6 +173,7 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
   if (mode != DFS_SELECT_TOPK && mode != DFS_SELECT_MASS_HEAD) return fail(DFS_EINVAL, "dfs_select_mask: unknown mode %d", mode);
   if (!(sparsity >= 0.0 && sparsity <= 1.0)) return fail(DFS_EINVAL, "dfs_select_mask: sparsity %g is outside [0,1]", sparsity);
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
+  if (s.M_v > 16384) return fail(DFS_ESHAPE, "dfs_select_mask: M_v=%d exceeds 16384 (one score row must fit in 64 KB of LDS)", s.M_v);
   const int k_base = dfs_keep_count(sparsity, s.M_v);
   if (K_max < k_base + s.M_x)
     return fail(DFS_ESHAPE, "dfs_select_mask: K_max=%d is below the %d kept blocks per row", K_max, k_base + s.M_x);

@@ -180,6 +180,9 @@ def _compare_attention(w, g, dt, qp_d, kp_d, vp_d, st, mask_np, blk_valid, q_blo
         oh = G.as_f64_dev(o_d[h]); lh = lse_d[h].cpu().numpy().astype(np.float64)
         for u in q_blocks:
             cols = np.nonzero(mask_np[h, u])[0]
+            if cols.size == 0:                                     # nothing kept: zero rows, lse = -inf
+                assert np.all(oh[u * w.B:(u + 1) * w.B] == 0) and np.all(np.isneginf(lh[u * w.B:(u + 1) * w.B]))
+                continue
             want, lse_w = O.sparse_attn_block(qh, kh, vh, cols, blk_valid, w.B, u, 1.0 / math.sqrt(w.d))
             rows = slice(u * w.B, u * w.B + blk_valid[u])          # pad query rows are not compared
             err = np.abs(oh[rows] - want[:blk_valid[u]])
