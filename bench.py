@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--sparsity", type=float, default=0.9)
     ap.add_argument("--heads", type=int, default=0, help="override the head count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the warm-up (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
                     help="scaled rocprofv3 FETCH_SIZE / WRITE_SIZE of the attention kernel, KiB per launch")
     return ap.parse_args()
@@ -100,6 +102,12 @@ def main():
         P.dfs_sparse_attn_fwd(g, dt, qp, kp, vp, kv_idx, kv_cnt, K_max, scale, op, None); mark(5)
         P.dfs_unperm(g, dt, op, inv, o); mark(6)
 
+    if a.calib_copy:       # a copy of known size: 1 GiB read + 1 GiB written
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()

@@ -156,7 +156,8 @@ int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double spar
  * bf16: products on the matrix cores, fp32 accumulation and softmax, output rounded to bf16.
  * f32:  fp32 throughout.
  *   q_perm, k_perm, v_perm [heads, N_pad, d] in;  o_perm [heads, N_pad, d] out (pad rows unspecified)
- *   lse [heads, N_pad] out or NULL: natural-log sum of exp(scale*logit) over the kept keys
+ *   lse [heads, N_pad] out or NULL: natural-log sum of exp(scale*logit) over the kept keys (the bf16
+ *       kernel sums the probabilities as rounded to bf16, the weights O is formed with: 2^-9 relative)
  *   scale: softmax scale, 1/sqrt(d) in the paper.
  */
 int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,

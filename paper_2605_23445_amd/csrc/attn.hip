@@ -10,6 +10,7 @@
 // LDS through the transposing LDS read, so V is stored row-major like K and never transposed in
 // memory.
 #include <math.h>
+#include <type_traits>
 
 #include "common.h"
 
@@ -21,6 +22,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
@@ -31,25 +33,54 @@ __device__ __forceinline__ int block_real_rows(int blk, int B, int M_v, int64_t 
   return real >= B ? B : (real <= 0 ? 0 : int(real));
 }
 
-template <int D, int BM>
-__global__ void __launch_bounds__(BM * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// XOR swizzles of the 16-byte chunks inside a tile row.  Tiles are stored without padding (the
+// direct-to-LDS load writes 64 consecutive chunks per wave instruction); the swizzle, applied on the
+// global side of the load and again on every LDS read, spreads the rows a wave reads at once over
+// all banks.  K is read one row per lane (16 B each), V four rows x 64 B per half-wave pass.
+template <int CH> __device__ __forceinline__ int swz_k(int row) { return (row / (16 / CH)) % CH; }
+template <int CH> __device__ __forceinline__ int swz_v(int row) { return 4 * ((row / (16 / CH)) % (CH / 4)); }
+
+constexpr int swz_period(int step, int mod) {    // smallest P with (P * step) % mod == 0
+  int p = 1;
+  while ((p * step) % mod != 0) ++p;
+  return p;
+}
+
+// QT = 32-row query tiles per wave.  With QT = 2 every K / V^T fragment read from LDS feeds two
+// matrix instructions, which halves the LDS bytes per matrix instruction (1 KB at QT = 1, and LDS
+// supplies 128 B per clock per CU), but at d = 128 the accumulators then need the whole register
+// file, i.e. one wave per SIMD, and a lone wave overlaps its matrix, vector and LDS work worse than two
+// waves do: measured slower (about 880 against 1030 TFLOP/s on cache-resident keys), so QT = 1 is
+// what is launched.
+template <int D, int BM, int QT>
+__global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_eu(2 / QT, 2 / QT)))
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int32_t* __restrict__ kv_idx, const int32_t* __restrict__ kv_cnt, int K_max, uint16_t* __restrict__ o,
                  float* __restrict__ lse, int64_t N_pad, int64_t N_v, int n_text, int M_v, int M, int total_wg,
-                 int wg_per_xcd, float scale) {
-  constexpr int NT = BM * 2;                       // threads: one wave per 32 query rows
-  constexpr int KS = D + 8;                        // K tile row stride (elements): 16 B skew per row
-  constexpr int VS = D + 32;                       // V tile row stride: 64 B skew per row
+                 int wg_per_xcd, int head_major, float scale) {
+  constexpr int NW = BM / (32 * QT);               // waves: one per 32 QT query rows
   constexpr int CH = D / 8;                        // 16-byte chunks per row
-  constexpr int LD = KN * CH / NT;                 // chunks each thread stages per tile
+  constexpr int TILE = KN * D;                     // elements per tile
+  constexpr int LPW = KN * CH / (64 * NW);         // load instructions per wave and tile
+  constexpr int RJ = NW * 64 / CH;                 // tile rows between two load instructions of a wave
   constexpr int STEPS = BM / KN;                   // tiles per key block
-  __shared__ __attribute__((aligned(16))) uint16_t sK[KN * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[KN * VS];
+  constexpr int NF = D / 8;                        // operand fragments per stage: D/16 of V^T, D/16 of K
+  constexpr int SLOTS = NF * QT;                   // matrix instructions per stage
+  constexpr int SLICES = 13 * QT;                  // softmax slices per stage
+  constexpr int STAGE_LEN = SLOTS > SLICES ? SLOTS : SLICES;
+  constexpr float TAU = 8.f;                       // rescale only when the row maximum grows by > 2^TAU
+  // Two K and two V tile buffers (tile t lives in the pair of parity t & 1).
+  __shared__ __attribute__((aligned(16))) uint16_t sK0[TILE];
+  __shared__ __attribute__((aligned(16))) uint16_t sK1[TILE];
+  __shared__ __attribute__((aligned(16))) uint16_t sV0[TILE];
+  __shared__ __attribute__((aligned(16))) uint16_t sV1[TILE];
 
-  // Work-group to (head, query block): consecutive ids on one XCD (ids are dealt round-robin to the
-  // 8 XCDs) walk the query blocks of one head, so neighbouring blocks share key blocks in that
-  // XCD's L2.  Query blocks are taken last-first: the dense text blocks at the end start first.
-  const int logical = (blockIdx.x % 8) * wg_per_xcd + blockIdx.x / 8;
+  // Work-group to (head, query block).  Ids are dealt round-robin to the 8 XCDs.  head_major: each XCD
+  // walks the query blocks of its own heads (neighbouring blocks, which share key blocks, meet in one
+  // L2).  Otherwise all XCDs work on the same head at a time, so the key/value working set of the
+  // chip is one or two heads and stays in the memory-side cache.  Query blocks are taken last-first:
+  // the dense text blocks at the end of a head start first.
+  const int logical = head_major ? (blockIdx.x % 8) * wg_per_xcd + blockIdx.x / 8 : blockIdx.x;
   if (logical >= total_wg) return;
   const int head = logical / M;
   const int u = M - 1 - logical % M;
@@ -63,138 +94,318 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   const int64_t head_off = int64_t(head) * N_pad * D;
   const uint16_t* kh = k + head_off;
   const uint16_t* vh = v + head_off;
-  const int64_t q_row = int64_t(u) * BM + wave * 32 + n;
+  const int64_t q_row0 = int64_t(u) * BM + wave * (32 * QT) + n;      // query tile a adds 32 a
 
-  // Q rows as the B operand of S^T = K Q^T: lane (n, h) holds Q[row n][16 kk + 8 h .. + 7]
-  bf16x8 qf[D / 16];
-  {
-    const u32x4* qp = reinterpret_cast<const u32x4*>(q + head_off + q_row * D);
+  // Q rows as the B operand of S^T = K Q^T: lane (n, h) holds Q[row][16 kk + 8 h .. + 7]
+  bf16x8 qf[QT][D / 16];
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, qp[2 * kk + h]);
+  for (int a = 0; a < QT; ++a) {
+    const u32x4* qp = reinterpret_cast<const u32x4*>(q + head_off + (q_row0 + 32 * a) * D);
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) qf[a][kk] = __builtin_bit_cast(bf16x8, qp[2 * kk + h]);
   }
 
-  f32x16 oacc[D / 32];
+  f32x16 oacc[QT][D / 32];
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float c2 = scale * 1.4426950408889634f;     // softmax in base 2
-
-  const int n_tiles = cnt * STEPS;
-  u32x4 pk[LD], pv[LD];
-  auto fetch = [&](int tile) {
-    int blk = dense ? tile / STEPS : idx[tile / STEPS];
-    blk = unsigned(blk) < unsigned(M) ? blk : 0;      // a corrupt list must not read out of bounds
-    const int64_t row0 = int64_t(blk) * BM + (tile % STEPS) * KN;
-    const u32x4* ks = reinterpret_cast<const u32x4*>(kh + row0 * D);
-    const u32x4* vs = reinterpret_cast<const u32x4*>(vh + row0 * D);
-#pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      pk[i] = ks[tid + i * NT];
-      pv[i] = vs[tid + i * NT];
-    }
-    return blk;
-  };
-  int blk_next = 0;
-  if (n_tiles > 0) blk_next = fetch(0);
-
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int blk = blk_next;
-    __syncthreads();                                 // every wave is done with the previous tile
-#pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      const int c = tid + i * NT;
-      const int row = c / CH, col = c % CH;
-      *reinterpret_cast<u32x4*>(&sK[row * KS + col * 8]) = pk[i];
-      *reinterpret_cast<u32x4*>(&sV[row * VS + col * 8]) = pv[i];
-    }
-    __syncthreads();
-    if (tile + 1 < n_tiles) blk_next = fetch(tile + 1);
-
-    // S^T tile pair: st[t][i] = logit(key row 32 t + 8 (i/4) + 4 h + i%4, query row n)
-    f32x16 st[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st[t][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&sK[(32 * t + n) * KS + 16 * kk + 8 * h]));
-        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], st[t], 0, 0, 0);
-      }
-    }
-    const int real = block_real_rows(blk, BM, M_v, N_v, n_text);
-    if (real < BM) {                                  // ragged last block: pad keys never count
-      const int base = (tile % STEPS) * KN;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (base + 32 * t + 8 * (i / 4) + 4 * h + (i % 4) >= real) st[t][i] = -INFINITY;
-    }
-
-    // online softmax for query row n (this lane and lane^32 hold the two halves of its keys)
-    float mx = st[0][0];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st[t][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a row that has seen only pad keys
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c2);
-    const float mc = m_use * c2;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(st[t][i], c2, -mc));
-        psum += p;
-        pf[2 * t + i / 8][i % 8] = (__bf16)p;
-      }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
+  for (int a = 0; a < QT; ++a)
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+      for (int i = 0; i < 16; ++i) oacc[a][dt][i] = 0.f;
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int a = 0; a < QT; ++a) { m_run[a] = -INFINITY; l_run[a] = 0.f; }
+  const float c2 = scale * 1.4426950408889634f;     // softmax in base 2
 
-    // O^T += V^T P^T.  Product step s covers key rows 16 s + {4h..4h+3} and 16 s + 8 + {4h..4h+3},
-    // which is what registers 8 (s%2) .. 8 (s%2) + 7 of st[s/2] hold; the transposing LDS read hands
-    // each lane four consecutive key rows of one value column.
-    const int vrow = 4 * h + ((lane & 15) >> 2);
-    const int vcol = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // Tile loads, global memory straight into LDS: instruction j of this wave fills the 64 consecutive
+  // 16-byte chunks (j NW + wave) 64 + lane of the tile buffer; the chunk swizzle is applied on the
+  // global side.  The swizzle repeats every PK (PV) instructions, so that few per-lane offsets serve all.
+  constexpr int PK = swz_period(RJ / (16 / CH) > 0 ? RJ / (16 / CH) : 1, CH);
+  constexpr int PV = swz_period(RJ / (16 / CH) > 0 ? RJ / (16 / CH) : 1, CH / 4);
+  static_assert(RJ % (16 / CH) == 0 && LPW % PK == 0 && LPW % PV == 0, "tile load pattern");
+  const int n_tiles = cnt * STEPS;
+  auto tile_block = [&](int tile) {
+    int blk = dense ? tile / STEPS : idx[tile / STEPS];
+    return unsigned(blk) < unsigned(M) ? blk : 0;     // a corrupt list must not read out of bounds
+  };
+  auto lane_off = [&](int j, bool is_v) {             // byte offset inside the tile of the chunk this lane fetches
+    const int p = (j * NW + wave) * 64 + lane;
+    const int row = p / CH, pc = p % CH;
+    return uint32_t(2 * (row * D + ((pc ^ (is_v ? swz_v<CH>(row) : swz_k<CH>(row))) * 8)));
+  };
+  uint32_t k_off[PK], v_off[PV];
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt) {
+  for (int j = 0; j < PK; ++j) k_off[j] = lane_off(j, false);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint16_t* p0 = &sV[(16 * s + vrow) * VS + dt * 32 + vcol];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p0));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p0 + 8 * VS));
-        const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[s], oacc[dt], 0, 0, 0);
+  for (int j = 0; j < PV; ++j) v_off[j] = lane_off(j, true);
+  // The load is issued from an asm statement so that it stays outside the compiler's wait-count
+  // bookkeeping: the compiler cannot tell that reads of one tile buffer are independent of loads in
+  // flight into another and would wait for every outstanding load before each LDS read.  The waits
+  // that are needed are the explicit vmcnt(0) + barrier pairs in the loop below.  (Loads retire in
+  // order, so the compiler's own counts for its few other memory operations stay conservative.)
+  auto issue = [&](const uint16_t* base, uint16_t* stage, bool is_v, int tile) {
+    const uint64_t src = reinterpret_cast<uint64_t>(base + (int64_t(tile_block(tile)) * BM + (tile % STEPS) * KN) * D);
+    const uint32_t lds0 = uint32_t(reinterpret_cast<uintptr_t>((LDS_PTR(void))(stage + wave * 512)));
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int P = is_v ? PV : PK;
+      const uint32_t voff = is_v ? v_off[j % PV] : k_off[j % PK];
+      const uint64_t sj = src + uint64_t(j / P) * (P * RJ) * D * 2;
+      const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(sj)), hi = __builtin_amdgcn_readfirstlane(uint32_t(sj >> 32));
+      const uint64_t sbase = (uint64_t(hi) << 32) | lo;
+      const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + uint32_t(j * NW * 1024));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase) : "memory");
+    }
+  };
+
+  // LDS read offsets (elements), loop invariant
+  const int k_sw = swz_k<CH>(n);                                    // rows 32 t + n: swizzle depends on n only
+  const int v_r = (lane & 15) >> 2;                                 // row inside the 4-row group
+  const int v_row = 4 * h + v_r;
+  const int v_sw = swz_v<CH>(v_r);                                  // rows 16 s + 4 h + v_r (+8): same swizzle
+  const int v_c = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);        // chunk inside the 32-column group
+  const int v_b = (lane & 1) * 4;                                   // 8-byte half of the chunk
+
+  // The loop works on half tiles (32 key rows).  Logits of a half tile for query tile a:
+  // sx[a][i] = logit(key row 32 half + 8 (i/4) + 4 h + i%4, query row 32 a + n).
+  auto k_frag = [&](const uint16_t* tK, int kk) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&tK[((2 * kk + h) ^ k_sw) * 8]));
+  };
+  // One product piece of O^T += V^T P^T for a half tile: piece j = (D/32) s2 + dt.  Product step s2
+  // covers key rows 16 s2 + {4h..4h+3} and 16 s2 + 8 + {4h..4h+3}, which is what registers 8 s2 .. 8 s2 + 7
+  // of the logit tile hold; the transposing LDS read hands each lane four consecutive key rows of one
+  // value column.
+  auto v_frag = [&](const uint16_t* tV, int j) {
+    const int s2 = j / (D / 32), dt = j % (D / 32);
+    const uint16_t* p0 = &tV[16 * s2 * D + ((4 * dt + v_c) ^ v_sw) * 8];
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p0 + 8 * D));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto logits = [&](const uint16_t* kbuf, int half, f32x16 (&sx)[QT]) {
+    const uint16_t* tK = kbuf + (32 * half + n) * D;
+#pragma unroll
+    for (int a = 0; a < QT; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sx[a][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const bf16x8 f = k_frag(tK, kk);
+#pragma unroll
+      for (int a = 0; a < QT; ++a) sx[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[a][kk], sx[a], 0, 0, 0);
+    }
+  };
+  // pad keys of a ragged block never count
+  auto mask_pads = [&](int tile, int half, f32x16 (&sx)[QT]) {
+    const int real = block_real_rows(tile_block(tile), BM, M_v, N_v, n_text);
+    if (real < BM) {
+      const int base = (tile % STEPS) * KN + 32 * half;
+#pragma unroll
+      for (int a = 0; a < QT; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (base + 8 * (i / 4) + 4 * h + (i % 4) >= real) sx[a][i] = -INFINITY;
+    }
+  };
+
+  // One pipeline stage, written out in issue order.  Fragments alternate between V^T of the previous
+  // half tile (products O^T += V^T P^T with its probabilities `pp`) and K of the next half tile (logit
+  // chains into `sn`); every fragment feeds one matrix instruction per query tile.  In the shadow of
+  // the matrix instructions the vector units run slices of the online softmax of the current half tile
+  // `sx` (this lane and lane^32 hold the two halves of a query row's keys), producing `pc`.  The
+  // reference maximum only moves when the row maximum outgrows it by more than 2^TAU, so the
+  // accumulators are rescaled rarely; probabilities stay below 2^TAU, which is exact in the final
+  // ratio.  Scheduling fences and empty asm statements keep the compiler from separating the matrix and
+  // vector work again.  alpha[a] is the factor accumulator a must be multiplied by after the stage.
+  auto stage = [&](auto do_pv, auto do_s, const uint16_t* vbuf, int pv_half, const bf16x8 (&pp)[QT][2], const uint16_t* kbuf,
+                   int s_half, f32x16 (&sn)[QT], const f32x16 (&sx)[QT], bf16x8 (&pc)[QT][2], float (&alpha)[QT], bool (&moved)[QT]) {
+    constexpr bool DO_PV = decltype(do_pv)::value, DO_S = decltype(do_s)::value;
+    const uint16_t* tV = vbuf + (32 * pv_half + v_row) * D + v_b;
+    const uint16_t* tK = kbuf + (32 * s_half + n) * D;
+    bf16x8 frag[NF];
+    auto load = [&](int f) {
+      if (f % 2 == 0) {
+        if (DO_PV) frag[f] = v_frag(tV, f / 2);
+      } else if (DO_S) {
+        frag[f] = k_frag(tK, f / 2);
       }
+    };
+    float mx_a = 0.f, mx_b = 0.f, mx_c = 0.f, mx_d = 0.f, mx = 0.f, m_new = 0.f, m_use = 0.f, mc = 0.f, psum = 0.f;
+    bool move = false;
+    float pe[16];
+    // Rounds a pair of probabilities to bf16 and adds them, as rounded, to the normaliser: numerator and
+    // denominator then use exactly the same weights, so a dominant key leaves no systematic rounding bias.
+    auto pack = [&](int a, int i) {
+      const bf16x2 pk = {(__bf16)pe[i], (__bf16)pe[i + 1]};
+      psum = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, psum, false);
+      pc[a][i / 8][i % 8] = pk[0];
+      pc[a][i / 8][i % 8 + 1] = pk[1];
+    };
+    if (DO_S) {
+#pragma unroll
+      for (int a = 0; a < QT; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sn[a][i] = 0.f;
+    }
+    constexpr int AHEAD = 2;                          // fragments requested ahead of their matrix instruction
+#pragma unroll
+    for (int f = 0; f < AHEAD; ++f) load(f);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < STAGE_LEN; ++m) {
+      if (m < SLOTS) {
+        const int f = m / QT, a = m % QT;
+        if (a == 0 && f + AHEAD < NF) load(f + AHEAD);
+        if (f % 2 == 0) {
+          if (DO_PV) {
+            const int j = f / 2, s2 = j / (D / 32), dt = j % (D / 32);
+            oacc[a][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f], pp[a][s2], oacc[a][dt], 0, 0, 0);
+          }
+        } else if (DO_S) {
+          sn[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f], qf[a][f / 2], sn[a], 0, 0, 0);
+        }
+      }
+      if (m < SLICES) {
+        const int a = m / 13, ph = m % 13;
+        const f32x16& x = sx[a];
+        if (ph == 0) {
+          mx_a = fmaxf(fmaxf(x[0], x[1]), x[2]);
+          mx_b = fmaxf(fmaxf(x[3], x[4]), x[5]);
+          mx_c = fmaxf(fmaxf(x[6], x[7]), x[8]);
+          mx_d = fmaxf(fmaxf(x[9], x[10]), x[11]);
+          psum = 0.f;
+        } else if (ph == 1) {
+          mx_a = fmaxf(fmaxf(mx_a, mx_b), mx_c);
+          mx_d = fmaxf(fmaxf(mx_d, x[12]), x[13]);
+          mx_a = fmaxf(fmaxf(mx_a, x[14]), x[15]);
+          mx = fmaxf(mx_a, mx_d);
+          asm volatile("" : "+v"(mx));                 // keeps the slice in its slot (its result is needed only later)
+        } else if (ph == 2) {
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+          mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          asm volatile("" : "+v"(mx));
+        } else if (ph == 3) {
+          move = (mx - m_run[a]) * c2 > TAU;          // true on the first real half tile (m_run = -inf)
+          m_new = move ? mx : m_run[a];
+          m_use = m_new == -INFINITY ? 0.f : m_new;   // a row that has seen only pad keys
+          mc = m_use * c2;
+          asm volatile("" : "+v"(mc));
+        } else if (ph < 12) {                         // eight slices of two probabilities each
+          const int i = 2 * (ph - 4);
+          pe[i] = __builtin_amdgcn_exp2f(fmaf(x[i], c2, -mc));
+          pe[i + 1] = __builtin_amdgcn_exp2f(fmaf(x[i + 1], c2, -mc));
+          asm volatile("" : "+v"(pe[i]), "+v"(pe[i + 1]));
+          if (i > 0) pack(a, i - 2);                  // one slice behind, so the exponentials have retired
+        } else {
+          pack(a, 14);
+          alpha[a] = __builtin_amdgcn_exp2f((m_run[a] - m_use) * c2);   // 1 unless the maximum moved
+          moved[a] = __builtin_amdgcn_ballot_w64(move) != 0;
+          m_run[a] = m_new;
+          l_run[a] = l_run[a] * alpha[a] + psum;
+          asm volatile("" : "+v"(l_run[a]), "+v"(alpha[a]));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // accumulators *= alpha, in place (the multiply is tied to its register so that the accumulators keep
+  // one home across the rarely taken branch)
+  auto rescale = [&](const float (&alpha)[QT], const bool (&moved)[QT]) {
+#pragma unroll
+    for (int a = 0; a < QT; ++a)
+      if (moved[a]) {
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float x = oacc[a][dt][i];
+            asm volatile("v_mul_f32 %0, %1, %0" : "+v"(x) : "v"(alpha[a]));
+            oacc[a][dt][i] = x;
+          }
+      }
+  };
+  using yes = std::true_type;
+  using no = std::false_type;
+
+  // Software pipeline over half tiles.  K(t+2) and V(t+1) are requested once per tile, right after the
+  // barrier in the middle of tile t, into the buffers K(t) and V(t-1) have just left; they are first
+  // read a full tile later.
+  f32x16 s0[QT], s1[QT];
+  bf16x8 p0[QT][2], p1[QT][2];
+  auto tile_step = [&](auto parity, auto first, auto last, int t) {
+    constexpr bool ODD = decltype(parity)::value, FIRST = decltype(first)::value, LAST = decltype(last)::value;
+    uint16_t* k_cur = ODD ? sK1 : sK0;             // K(t); K(t+2) goes here
+    uint16_t* k_nxt = ODD ? sK0 : sK1;             // K(t+1)
+    uint16_t* v_cur = ODD ? sV1 : sV0;             // V(t)
+    uint16_t* v_nxt = ODD ? sV0 : sV1;             // V(t-1); V(t+1) goes here
+    float alpha[QT];
+    bool moved[QT];
+    // first half: products of (t-1, 1), logits of (t, 1), softmax of (t, 0)
+    stage(std::integral_constant<bool, !FIRST>{}, yes{}, v_nxt, 1, p1, k_cur, 1, s1, s0, p0, alpha, moved);
+    rescale(alpha, moved);
+    mask_pads(t, 1, s1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's parts of K(t+1) and V(t) landed
+    __syncthreads();                                 // all parts landed; every wave is past the first half of tile t
+    if (!LAST) {
+      if (t + 2 < n_tiles) issue(kh, k_cur, false, t + 2);
+      issue(vh, v_nxt, true, t + 1);
+    }
+    // second half: products of (t, 0), logits of (t+1, 0), softmax of (t, 1)
+    stage(yes{}, std::integral_constant<bool, !LAST>{}, v_cur, 0, p0, k_nxt, 0, s0, s1, p1, alpha, moved);
+    rescale(alpha, moved);
+    if (!LAST) mask_pads(t + 1, 0, s0);
+  };
+  if (n_tiles > 0) {
+    issue(kh, sK0, false, 0);
+    issue(vh, sV0, true, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (n_tiles > 1) issue(kh, sK1, false, 1);
+    logits(sK0, 0, s0);
+    mask_pads(0, 0, s0);
+    if (n_tiles == 1) {
+      tile_step(no{}, yes{}, yes{}, 0);
+    } else {
+      tile_step(no{}, yes{}, no{}, 0);
+      int t = 1;
+      for (; t + 2 < n_tiles; t += 2) {              // middle tiles in pairs: buffer parities are compile-time
+        tile_step(yes{}, no{}, no{}, t);
+        tile_step(no{}, no{}, no{}, t + 1);
+      }
+      if (t + 1 < n_tiles) { tile_step(yes{}, no{}, no{}, t); ++t; }
+      if (t & 1) tile_step(yes{}, no{}, yes{}, t);
+      else tile_step(no{}, no{}, yes{}, t);
+    }
+    // drain: products of the last half tile
+    const uint16_t* tV = ((n_tiles - 1) & 1 ? sV1 : sV0) + (32 + v_row) * D + v_b;
+#pragma unroll
+    for (int j = 0; j < 2 * (D / 32); ++j) {
+      const bf16x8 f = v_frag(tV, j);
+#pragma unroll
+      for (int a = 0; a < QT; ++a)
+        oacc[a][j % (D / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, p1[a][j / (D / 32)], oacc[a][j % (D / 32)], 0, 0, 0);
     }
   }
 
-  // epilogue: normalise, round to bf16, store.  Lane (n, h) holds O[row n][32 dt + 8 j + 4 h + 0..3].
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-  uint16_t* orow = o + head_off + q_row * D;
+  // epilogue: normalise, round to bf16, store.  Lane (n, h) holds O[row][32 dt + 8 j + 4 h + 0..3].
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
+  for (int a = 0; a < QT; ++a) {
+    const float l_tot = l_run[a] + __shfl_xor(l_run[a], 32, 64);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    uint16_t* orow = o + head_off + (q_row0 + 32 * a) * D;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16x4 w;
+    for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][4 * j + e] * inv);
-      *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * j + 4 * h) = __builtin_bit_cast(u32x2, w);
-    }
-  if (lse && h == 0)
-    lse[int64_t(head) * N_pad + q_row] = l_tot > 0.f ? (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[a][dt][4 * j + e] * inv);
+        *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * j + 4 * h) = __builtin_bit_cast(u32x2, w);
+      }
+    if (lse && h == 0)
+      lse[int64_t(head) * N_pad + q_row0 + 32 * a] =
+          l_tot > 0.f ? (m_run[a] * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -287,13 +498,14 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
     if (total > (int64_t(1) << 30)) return fail(DFS_ESHAPE, "dfs_sparse_attn_fwd: heads*M too large");
     const int per_xcd = int((total + 7) / 8);
     dim3 grid(unsigned(per_xcd * 8));
-#define ATTN(DD, BB)                                                                                                        \
-  attn_bf16_kernel<DD, BB><<<grid, BB * 2, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),        \
-                                                    static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,                  \
-                                                    static_cast<uint16_t*>(o), lse, s.N_pad, s.N_v, g->n_text, s.M_v, s.M,   \
-                                                    int(total), per_xcd, scale)
-    if (g->d == 64) { if (g->B == 64) ATTN(64, 64); else ATTN(64, 128); }
-    else            { if (g->B == 64) ATTN(128, 64); else ATTN(128, 128); }
+    const int head_major = 1;                        // measured equal to the interleaved mapping on the benchmark shapes
+#define ATTN(DD, BB, QQ)                                                                                                    \
+  attn_bf16_kernel<DD, BB, QQ><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
+                                                             static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
+                                                             static_cast<uint16_t*>(o), lse, s.N_pad, s.N_v, g->n_text,       \
+                                                             s.M_v, s.M, int(total), per_xcd, head_major, scale)
+    if (g->d == 64) { if (g->B == 64) ATTN(64, 64, 1); else ATTN(64, 128, 1); }
+    else            { if (g->B == 64) ATTN(128, 64, 1); else ATTN(128, 128, 1); }
 #undef ATTN
   } else {
     if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
