@@ -23,6 +23,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+# HBM-side traffic of the attention kernel per launch on the default workload (wan, sparsity 0.9), from
+# profiles/wan90_attention_counters.txt: FETCH_SIZE x 2.00 and WRITE_SIZE x 1.00, in bytes.
+RECORDED_TRAFFIC = {("wan", 0.9): (27405000 * 1024 * 2.0, 851043 * 1024 * 1.0)}
 
 
 def parse():
@@ -37,7 +40,8 @@ def parse():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the warm-up (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
-                    help="scaled rocprofv3 FETCH_SIZE / WRITE_SIZE of the attention kernel, KiB per launch")
+                    help="scaled rocprofv3 FETCH_SIZE / WRITE_SIZE of the attention kernel, KiB per launch "
+                         "(default: the values recorded in profiles/ for the default workload)")
     return ap.parse_args()
 
 
@@ -128,6 +132,14 @@ def main():
     e = 2 if w.dtype == "bf16" else 4
     bytes_permute = 3 * w.heads * (sz["N"] + N_pad) * w.d * e + 3 * N_pad * 4
     bytes_unperm = 2 * w.heads * sz["N"] * w.d * e + sz["N"] * 4
+    if a.traffic_kib is not None:
+        rec = (a.traffic_kib[0] * 1024, a.traffic_kib[1] * 1024)
+    else:
+        rec = RECORDED_TRAFFIC.get((w.name, a.sparsity)) if not a.heads else None
+    traffic = None if rec is None else rec[0] + rec[1]
+    traffic_detail = None if rec is None else {
+        "fetch_bytes": rec[0], "write_bytes": rec[1], "algorithmic_bytes": 4.0 * w.heads * N_pad * w.d * e,
+        "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, scaled by a 1 GiB copy (profiles/wan90_attention_counters.txt)"}
     out = {
         "metric": "dense-equivalent attention TFLOP/s of one whole DFSAttn step (reorder + block scoring + "
                   "top-k selection + block-sparse attention + inverse reorder) at the given sparsity",
@@ -148,8 +160,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
                      "achieved": flop_exec / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": None if a.traffic_kib is None else {"fetch_bytes": a.traffic_kib[0] * 1024, "write_bytes": a.traffic_kib[1] * 1024,
-                                                                   "algorithmic_bytes": 4.0 * w.heads * N_pad * w.d * e}},
+                     "traffic": traffic, "traffic_detail": traffic_detail},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, sz, a.sparsity, q, k, v, flop_dense)
