@@ -1,11 +1,17 @@
 // Hierarchical block scoring (paper Sec. 5.2; Algorithm 1 step 2; Eq. 2 and Eq. 8).
 //
-//   pool_kernel   : Q_hat, K_hat = mean over the real rows of each sub-block (fp32), an HBM stream.
+//   pool_kernel   : Q_hat, K_hat = mean over the real rows of each sub-block, an HBM stream.  The fp32
+//                   means (Q_hat already times 1/sqrt(d)) are stored split into three bf16 terms
+//                   x = hi + mid + lo, which together carry the 24 bits of the fp32 value.
 //   score_kernel  : S_hat[u,v] = sum over the r x r sub-block pairs of softmax(Q_hat K_hat^T / sqrt(d)).
-//                   The sub-block attention matrix A_hat is never stored: a work-group owns 32
-//                   query sub-blocks, runs over all key sub-blocks twice with fp32 matrix-core
-//                   products (first pass: row maximum and normaliser, second pass: normalised
-//                   probabilities folded r x r) and writes only the block scores.
+//                   The sub-block attention matrix A_hat is never stored: a work-group owns 128 query
+//                   sub-blocks (32 per wave) and walks all key sub-blocks twice (first pass: row maximum
+//                   and normaliser, second pass: normalised probabilities folded r x r), writing only the
+//                   block scores.  The logits run on the bf16 matrix cores as six partial products
+//                   hi.hi + hi.mid + mid.hi + hi.lo + lo.hi + mid.mid with fp32 accumulation: every
+//                   bf16 product is exact in fp32 and the dropped terms are below 2^-23 of the result, so
+//                   the logits are as accurate as an fp32 contraction at 2.7 times its speed (the mask
+//                   decision that follows stays an fp32 one).
 #include "common.h"
 
 namespace dfs {
@@ -13,15 +19,27 @@ namespace dfs {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // ------------------------------------------------------------------------------------ pooling
 
+// x -> (hi, mid, lo) with hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid); the subtractions are exact.
+__device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
+  hi = f32_to_bf16(x);
+  const float r1 = x - bf16_to_f32(hi);
+  mid = f32_to_bf16(r1);
+  const float r2 = r1 - bf16_to_f32(mid);
+  lo = f32_to_bf16(r2);
+}
+
 // One wave per sub-block.  Lanes of a row sit side by side (16 bytes each); several rows are in
 // flight per load; partial sums of the row groups are folded with cross-lane exchanges.
+// Output row layout: [3][D] bf16 (hi, mid, lo planes).
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_perm, const void* __restrict__ k_perm,
-                                                   float* __restrict__ q_hat, float* __restrict__ k_hat, int64_t N_pad,
-                                                   int64_t N_v, int Bs, int M_s) {
+                                                   uint16_t* __restrict__ q_hat, uint16_t* __restrict__ k_hat, int64_t N_pad,
+                                                   int64_t N_v, int Bs, int M_s, float q_scale) {
   constexpr int EPL = BF16 ? 8 : 4;           // elements per lane (16 bytes)
   constexpr int TPR = D / EPL;                // lanes per row
   constexpr int RPP = 64 / TPR;               // rows per pass
@@ -30,7 +48,7 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
   if (s >= M_s) return;
   const int head = blockIdx.y;
   const void* src = blockIdx.z == 0 ? q_perm : k_perm;
-  float* dst = blockIdx.z == 0 ? q_hat : k_hat;
+  uint16_t* dst = blockIdx.z == 0 ? q_hat : k_hat;
   const int c = lane % TPR, rg = lane / TPR;
   const int64_t row0 = int64_t(s) * Bs;
   int64_t left = N_v - row0;
@@ -58,12 +76,16 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
     for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
   }
   if (rg == 0) {
-    const float inv = cnt > 0 ? 1.0f / float(cnt) : 0.f;
-    float* o = dst + (int64_t(head) * M_s + s) * D + c * EPL;
+    const float inv = cnt > 0 ? (blockIdx.z == 0 ? q_scale : 1.0f) / float(cnt) : 0.f;
+    uint16_t* o = dst + (int64_t(head) * M_s + s) * (3 * D) + c * EPL;
+    uint16_t hi[EPL], mid[EPL], lo[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; e += 4) {
-      f32x4 w = {acc[e] * inv, acc[e + 1] * inv, acc[e + 2] * inv, acc[e + 3] * inv};
-      *reinterpret_cast<f32x4*>(o + e) = w;
+    for (int e = 0; e < EPL; ++e) split3(acc[e] * inv, hi[e], mid[e], lo[e]);
+#pragma unroll
+    for (int e = 0; e < EPL; e += 2) {
+      *reinterpret_cast<uint32_t*>(o + e) = uint32_t(hi[e]) | (uint32_t(hi[e + 1]) << 16);
+      *reinterpret_cast<uint32_t*>(o + D + e) = uint32_t(mid[e]) | (uint32_t(mid[e + 1]) << 16);
+      *reinterpret_cast<uint32_t*>(o + 2 * D + e) = uint32_t(lo[e]) | (uint32_t(lo[e + 1]) << 16);
     }
   }
 }
@@ -82,69 +104,90 @@ __device__ __forceinline__ void online_merge(float& m, float& z, float m2, float
   m = mx;
 }
 
-// logits of one 32 x 32 tile: rows = the work-group's query sub-blocks (held in `aq`), columns =
-// key sub-blocks col0 .. col0+31.  Feature index of product step (kk, half) is half*D/2 + kk for
-// both operands, so every lane reads D/2 consecutive floats of its key row.
 template <int D>
-__device__ __forceinline__ f32x16 logit_tile(const float (&aq)[D / 2], const float* __restrict__ k_hat_head, int col, int M_s,
-                                             int half) {
-  float bk[D / 2];
-  if (col < M_s) {
-    const f32x4* p = reinterpret_cast<const f32x4*>(k_hat_head + int64_t(col) * D + half * (D / 2));
-#pragma unroll
-    for (int j = 0; j < D / 8; ++j) {
-      const f32x4 v = p[j];
-      bk[4 * j] = v[0]; bk[4 * j + 1] = v[1]; bk[4 * j + 2] = v[2]; bk[4 * j + 3] = v[3];
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < D / 2; ++j) bk[j] = 0.f;
-  }
-  f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int kk = 0; kk < D / 2; ++kk) c = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[kk], bk[kk], c, 0, 0, 0);
-  return c;
-}
-
-template <int D>
-__global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_hat, const float* __restrict__ k_hat,
-                                                    float* __restrict__ score, int M_s, int M_v, int r, int n_live,
-                                                    float scale) {
-  __shared__ float s_m[4][32], s_z[4][32];
-  __shared__ float s_row_m[32], s_row_inv[32];
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+score_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, float* __restrict__ score, int M_s, int M_v,
+             int r, int n_live) {
+  constexpr int RS = 3 * D;                   // elements of a centroid row (hi, mid, lo planes)
+  constexpr int RSP = RS + 8;                 // LDS row stride: 16 bytes of skew keep the row-per-lane reads conflict-free
+  constexpr int KS = D / 16;                  // product steps of 16 features
+  constexpr int CPT = 32 * RS / 8 / 256;      // 16-byte chunks of a key tile per thread (6 at d=128)
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[32 * RSP];
   __shared__ float s_p[4][32][33];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col_l = lane & 31, half = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, half = lane >> 5;
   const int head = blockIdx.y;
-  const int i0 = blockIdx.x * 32;
-  const float* qh = q_hat + int64_t(head) * M_s * D;
-  const float* kh = k_hat + int64_t(head) * M_s * D;
+  const int i0 = blockIdx.x * 128 + wave * 32;   // first query sub-block of this wave
+  const uint16_t* qh = q_hat + int64_t(head) * M_s * RS;
+  const uint16_t* kh = k_hat + int64_t(head) * M_s * RS;
 
-  float aq[D / 2];
+  // Query centroids as the A operand: lane (n, half) holds row i0 + n, features 16 kk + 8 half .. + 7, three planes.
+  bf16x8 aq[3][KS];
   {
-    const int row = i0 + col_l;
-    if (row < M_s) {
-      const f32x4* p = reinterpret_cast<const f32x4*>(qh + int64_t(row) * D + half * (D / 2));
+    const int row = i0 + n;
 #pragma unroll
-      for (int j = 0; j < D / 8; ++j) {
-        const f32x4 v = p[j];
-        aq[4 * j] = v[0] * scale; aq[4 * j + 1] = v[1] * scale; aq[4 * j + 2] = v[2] * scale; aq[4 * j + 3] = v[3] * scale;
+    for (int p = 0; p < 3; ++p)
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row < M_s) v = *reinterpret_cast<const u32x4*>(qh + int64_t(row) * RS + p * D + 16 * kk + 8 * half);
+        aq[p][kk] = __builtin_bit_cast(bf16x8, v);
       }
-    } else {
-#pragma unroll
-      for (int j = 0; j < D / 2; ++j) aq[j] = 0.f;
-    }
   }
-  const int n_tiles = (n_live + 31) / 32;    // key sub-blocks at or beyond n_live are empty
+  const int n_tiles = (n_live + 31) / 32;     // key sub-blocks at or beyond n_live are empty
 
-  // pass 1: row maximum and normaliser.  Lane (col_l, half) holds rows 8*(i/4) + 4*half + i%4.
+  // key tile t (32 centroid rows, contiguous in memory) -> registers -> LDS
+  u32x4 stage[CPT];
+  auto fetch = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int c = tid + i * 256;
+      const int row = t * 32 + c / (RS / 8);
+      stage[i] = u32x4{0u, 0u, 0u, 0u};
+      if (row < M_s) stage[i] = *reinterpret_cast<const u32x4*>(kh + int64_t(t) * 32 * RS + int64_t(c) * 8);
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int c = tid + i * 256;
+      *reinterpret_cast<u32x4*>(&s_k[(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = stage[i];
+    }
+  };
+  // logits of the 32 x 32 tile: c[i] = <q_hat[row 8 (i/4) + 4 half + i%4], k_hat[column n]>
+  auto logit_tile = [&]() {
+    // three accumulators, so that consecutive matrix instructions never wait for each other's result
+    f32x16 sa = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 sb = sa, big = sa;
+    const uint16_t* krow = &s_k[n * RSP + 8 * half];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
+      const bf16x8 bm = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
+      const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 2 * D + 16 * kk));
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[2][kk], bh, sa, 0, 0, 0);     // lo.hi
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bl, sb, 0, 0, 0);     // hi.lo
+      big = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bh, big, 0, 0, 0);   // hi.hi
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[1][kk], bm, sa, 0, 0, 0);     // mid.mid
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[1][kk], bh, sb, 0, 0, 0);     // mid.hi
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bm, sa, 0, 0, 0);     // hi.mid
+    }
+    const f32x16 small = sa + sb;
+    return big + small;
+  };
+
+  // pass 1: row maximum and normaliser.  Lane (n, half) holds rows 8 (i/4) + 4 half + i%4 of column n.
   float m[16], z[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) { m[i] = -INFINITY; z[i] = 0.f; }
-  for (int t = wave; t < n_tiles; t += 4) {
-    const int col = t * 32 + col_l;
-    const f32x16 c = logit_tile<D>(aq, kh, col, M_s, half);
-    if (col < n_live) {
+  fetch(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();                          // every wave is done with the previous tile
+    commit();
+    __syncthreads();
+    if (t + 1 < n_tiles) fetch(t + 1);
+    const f32x16 c = logit_tile();
+    if (t * 32 + n < n_live) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) online_add(m[i], z[i], c[i]);
     }
@@ -157,86 +200,68 @@ __global__ void __launch_bounds__(256) score_kernel(const float* __restrict__ q_
       online_merge(m[i], z[i], m2, z2);
     }
   }
-  if (col_l == 0) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = 8 * (i / 4) + 4 * half + (i % 4);
-      s_m[wave][row] = m[i];
-      s_z[wave][row] = z[i];
-    }
-  }
-  __syncthreads();
-  if (threadIdx.x < 32) {
-    float mm = s_m[0][threadIdx.x], zz = s_z[0][threadIdx.x];
-    for (int w = 1; w < 4; ++w) online_merge(mm, zz, s_m[w][threadIdx.x], s_z[w][threadIdx.x]);
-    const int row = i0 + threadIdx.x;
-    s_row_m[threadIdx.x] = mm;
-    s_row_inv[threadIdx.x] = (row < n_live && zz > 0.f) ? 1.0f / zz : 0.f;   // empty query sub-blocks score nothing
-  }
-  __syncthreads();
-  float rm[16], rinv[16];
+  float rinv[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    const int row = 8 * (i / 4) + 4 * half + (i % 4);
-    rm[i] = s_row_m[row];
-    rinv[i] = s_row_inv[row];
+    const int row = i0 + 8 * (i / 4) + 4 * half + (i % 4);
+    rinv[i] = (row < n_live && z[i] > 0.f) ? 1.0f / z[i] : 0.f;   // empty query sub-blocks score nothing
   }
 
   // pass 2: probabilities, folded r x r into block scores
-  const int per = 32 / r;                    // blocks per tile edge
+  const int per = 32 / r;                     // blocks per tile edge
   const int u0 = i0 / r;
   float* out = score + int64_t(head) * M_v * M_v;
   const int n_tiles_all = (M_s + 31) / 32;
-  for (int tb = 0; tb < n_tiles_all; tb += 4) {   // trip count is the same for all four waves
-    const int t = tb + wave;
-    const int col = t * 32 + col_l;
+  fetch(0);
+  for (int t = 0; t < n_tiles_all; ++t) {
+    __syncthreads();
+    commit();
+    __syncthreads();
+    if (t + 1 < n_tiles_all) fetch(t + 1);
     if (t < n_tiles) {
-      const f32x16 c = logit_tile<D>(aq, kh, col, M_s, half);
+      const f32x16 c = logit_tile();
+      const bool live = t * 32 + n < n_live;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = 8 * (i / 4) + 4 * half + (i % 4);
-        s_p[wave][row][col_l] = col < n_live ? __expf(c[i] - rm[i]) * rinv[i] : 0.f;
-      }
+      for (int i = 0; i < 16; ++i) s_p[wave][8 * (i / 4) + 4 * half + (i % 4)][n] = live ? __expf(c[i] - m[i]) * rinv[i] : 0.f;
     } else {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s_p[wave][8 * (i / 4) + 4 * half + (i % 4)][col_l] = 0.f;
+      for (int i = 0; i < 16; ++i) s_p[wave][8 * (i / 4) + 4 * half + (i % 4)][n] = 0.f;
     }
-    __syncthreads();
-    if (t < n_tiles_all) {
-      for (int o = lane; o < per * per; o += 64) {
-        const int ur = o / per, vc = o % per;
-        float acc = 0.f;
-        for (int a = 0; a < r; ++a)
-          for (int b = 0; b < r; ++b) acc += s_p[wave][ur * r + a][vc * r + b];
-        const int u = u0 + ur, v = t * per + vc;
-        if (u < M_v && v < M_v) out[int64_t(u) * M_v + v] = acc;
-      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // s_p[wave] is private to this wave: order its writes before its reads
+    __builtin_amdgcn_wave_barrier();
+    for (int o = lane; o < per * per; o += 64) {
+      const int ur = o / per, vc = o % per;
+      float acc = 0.f;
+      for (int a = 0; a < r; ++a)
+        for (int b = 0; b < r; ++b) acc += s_p[wave][ur * r + a][vc * r + b];
+      const int u = u0 + ur, v = t * per + vc;
+      if (u < M_v && v < M_v) out[int64_t(u) * M_v + v] = acc;
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s) {
-  return 2 * align256(size_t(g->heads) * s.M_s * g->d * sizeof(float));
+  return 2 * align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t));
 }
 
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm, float* score,
                     void* ws, hipStream_t st) {
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
-  const size_t half = align256(size_t(g->heads) * s.M_s * g->d * sizeof(float));
-  float* q_hat = static_cast<float*>(ws);
-  float* k_hat = reinterpret_cast<float*>(static_cast<char*>(ws) + half);
+  const size_t half = align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t));
+  uint16_t* q_hat = static_cast<uint16_t*>(ws);
+  uint16_t* k_hat = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + half);
   dim3 pg(unsigned((s.M_s + 3) / 4), unsigned(g->heads), 2);
   const bool bf = dtype == DFS_BF16;
-#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, s.N_pad, s.N_v, g->Bs, s.M_s)
+  const float scale = 1.0f / sqrtf(float(g->d));
+#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
   if (g->d == 64) { if (bf) POOL(true, 64); else POOL(false, 64); }
   else            { if (bf) POOL(true, 128); else POOL(false, 128); }
 #undef POOL
   const int n_live = int((s.N_v + g->Bs - 1) / g->Bs);
-  const float scale = 1.0f / sqrtf(float(g->d));
-  dim3 sg(unsigned((s.M_s + 31) / 32), unsigned(g->heads));
-  if (g->d == 64) score_kernel<64><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live, scale);
-  else score_kernel<128><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live, scale);
+  dim3 sg(unsigned((s.M_s + 127) / 128), unsigned(g->heads));
+  if (g->d == 64) score_kernel<64><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live);
+  else score_kernel<128><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live);
   return launch_status("dfs_block_score");
 }
 
