@@ -32,22 +32,21 @@ def cube_bits(T: int, H: int, W: int) -> int:
     return max(1, int(max(T, H, W) - 1).bit_length())
 
 
-def hilbert_key(t, h, w, b: int):
-    """Hilbert index of the cells (t,h,w) in the cube [0,2^b)^3 (Sec. 5.1).
+def hilbert_key_nd(coords, b: int):
+    """Hilbert index of cells in the cube [0,2^b)^n, n = len(coords) (Sec. 5.1 for n = 3).
 
-    The paper names "a 3D Hilbert space-filling curve" without fixing which.  The
-    reading: Skilling's transpose form of the Butz curve with axes (x0,x1,x2) =
-    (t,h,w).  Working from the finest bit pair upward the coordinates are un-rotated
-    (A), then Gray-decoded (B), and the three b-bit words are read as b octal digits
-    with x0 the high bit of each digit (C).
+    The paper names "a 3D Hilbert space-filling curve" without fixing which.  The reading:
+    Skilling's transpose form of the Butz curve with the first coordinate the most significant.
+    Working from the coarsest bit downward the coordinates are un-rotated (A), then Gray-decoded
+    (B), and the n b-bit words are read as b digits of n bits with x0 the high bit of each (C).
     """
-    x = [np.array(t, dtype=np.int64).copy(), np.array(h, dtype=np.int64).copy(),
-         np.array(w, dtype=np.int64).copy()]
+    n = len(coords)
+    x = [np.array(c, dtype=np.int64).copy() for c in coords]
     # (A) undo the sub-cube rotations, coarsest level first
     Q = 1 << (b - 1)
     while Q > 1:
         P = Q - 1
-        for i in range(3):
+        for i in range(n):
             hi = (x[i] & Q) != 0
             # bit set: reflect the low bits of x0; clear: exchange low bits of x0 and xi
             s = np.where(hi, 0, (x[0] ^ x[i]) & P)
@@ -55,20 +54,71 @@ def hilbert_key(t, h, w, b: int):
             x[i] = x[i] ^ s
         Q >>= 1
     # (B) Gray decode across the axes
-    x[1] = x[1] ^ x[0]
-    x[2] = x[2] ^ x[1]
+    for i in range(1, n):
+        x[i] = x[i] ^ x[i - 1]
     s = np.zeros_like(x[0])
     Q = 1 << (b - 1)
     while Q > 1:
-        s = np.where((x[2] & Q) != 0, s ^ (Q - 1), s)
+        s = np.where((x[n - 1] & Q) != 0, s ^ (Q - 1), s)
         Q >>= 1
     x = [xi ^ s for xi in x]
-    # (C) interleave: octal digit j = 4*bit_j(x0) + 2*bit_j(x1) + bit_j(x2)
+    # (C) interleave: digit j = sum_i bit_j(x_i) << (n-1-i)
     key = np.zeros_like(x[0])
     for j in range(b - 1, -1, -1):
-        digit = (((x[0] >> j) & 1) << 2) | (((x[1] >> j) & 1) << 1) | ((x[2] >> j) & 1)
-        key = (key << 3) | digit
+        digit = np.zeros_like(x[0])
+        for i in range(n):
+            digit = (digit << 1) | ((x[i] >> j) & 1)
+        key = (key << n) | digit
     return key
+
+
+def hilbert_key(t, h, w, b: int):
+    """3D Hilbert index of the cells (t,h,w) in the cube [0,2^b)^3, axes (x0,x1,x2) = (t,h,w)."""
+    return hilbert_key_nd([t, h, w], b)
+
+
+ORDERS = ("hilbert3d", "raster", "hilbert2d", "block3d")
+
+
+def order_keys(kind: str, T: int, H: int, W: int):
+    """Sort key of every video token (raster index n) under a traversal order.
+
+    hilbert3d: the method's order (Sec. 5.1).  The others are the orderings of the ablation
+    (Sec. 6.3, Table 3): raster = per-frame row-major (the model's own order); hilbert2d = Hilbert
+    order inside each frame, frames in sequence; block3d = 4x4x4 cubes in raster order of the
+    cubes, raster traversal inside a cube.  Keys are distinct within a kind.
+    """
+    n = np.arange(T * H * W, dtype=np.int64)
+    t, h, w = n // (H * W), (n // W) % H, n % W
+    if kind == "hilbert3d":
+        return hilbert_key(t, h, w, cube_bits(T, H, W))
+    if kind == "raster":
+        return n
+    if kind == "hilbert2d":
+        b2 = cube_bits(1, H, W)
+        return (t << (2 * b2)) | hilbert_key_nd([h, w], b2)
+    if kind == "block3d":
+        ch, cw = -(-H // 4), -(-W // 4)
+        cube = ((t // 4) * ch + h // 4) * cw + w // 4
+        return cube * 64 + ((t % 4) * 4 + h % 4) * 4 + w % 4
+    raise ValueError(kind)
+
+
+def token_order(kind: str, T: int, H: int, W: int, n_text: int, B: int):
+    """Permutation and padded block layout for a traversal order (see hilbert_perm for the layout)."""
+    N_v = T * H * W
+    order = np.argsort(order_keys(kind, T, H, W), kind="stable")
+    M_v = -(-N_v // B)
+    M_x = -(-n_text // B)
+    M = M_v + M_x
+    perm_pad = np.full(M * B, -1, dtype=np.int32)
+    perm_pad[:N_v] = order
+    perm_pad[M_v * B: M_v * B + n_text] = N_v + np.arange(n_text)
+    inv = np.empty(N_v + n_text, dtype=np.int32)
+    pos = np.nonzero(perm_pad >= 0)[0]
+    inv[perm_pad[pos]] = pos
+    blk_valid = (perm_pad.reshape(M, B) >= 0).sum(axis=1).astype(np.int32)
+    return perm_pad, inv, blk_valid
 
 
 def hilbert_perm(T: int, H: int, W: int, n_text: int, B: int):
@@ -368,3 +418,44 @@ class DFSAttnOracle:
                 self.mask, _ = select_topk(score, sparsity, self.M_x)
         o_perm, _ = sparse_attn(qp, kp, vp, self.mask, self.blk_valid, self.B)
         return unpermute(o_perm, self.inv)
+
+
+# ----------------------------------------------------------------------------------------
+# Attention recall (Eq. 3) and the paper's step schedule (Sec. 5.3, Sec. 6.1, App. B)
+# ----------------------------------------------------------------------------------------
+
+
+def attention_recall(q_perm, k_perm, mask, blk_valid, B: int):
+    """R = ||A * M||_1 / ||A||_1 (Eq. 3) per head, with M the token-level form of the block mask and
+    A the full attention matrix of Eq. 1 over the real tokens: the mean over real query rows of the
+    attention mass that falls on kept key blocks.  q_perm, k_perm: [heads, N_pad, d] fp64."""
+    heads, N_pad, d = q_perm.shape
+    M = N_pad // B
+    real = np.concatenate([np.arange(u * B, u * B + blk_valid[u]) for u in range(M)])
+    blk_of = real // B
+    out = np.empty(heads)
+    for h in range(heads):
+        s = (q_perm[h][real] @ k_perm[h][real].T) / math.sqrt(d)
+        a = np.exp(s - s.max(axis=1, keepdims=True))
+        a /= a.sum(axis=1, keepdims=True)
+        keep = mask[h][blk_of][:, blk_of].astype(bool)     # token-level mask
+        out[h] = (a * keep).sum() / a.sum()
+    return out
+
+
+def paper_schedule(total_steps: int, t: int, delta: int = 12, dense_frac: float = 0.25, keep0: float = 0.3,
+                   keep_step: float = 0.1, cached_keep=None):
+    """What step t of a sampling run does (Sec. 6.1 "Implementation details", App. B; Alg. 1 for the refresh).
+
+    Steps in the first quarter run dense attention.  After that the keep ratio starts at keep0 and drops by
+    keep_step every further quarter (0.3 -> 0.2 -> 0.1, about 80 % mean sparsity).  The mask is recomputed
+    when t is a multiple of delta (Alg. 1) and, readings the paper leaves open, when no mask exists yet
+    (first sparse step) or when the cached mask was built for another keep ratio (`cached_keep`).
+    Returns (dense, refresh, sparsity).
+    """
+    quarter = min(int(math.floor(t / (dense_frac * total_steps) + 1e-9)), int(round(1 / dense_frac)) - 1)
+    if quarter == 0:
+        return True, False, 0.0
+    keep = keep0 - keep_step * (quarter - 1)
+    refresh = (t % delta == 0) or cached_keep is None or abs(cached_keep - keep) > 1e-12
+    return False, refresh, 1.0 - keep

@@ -1,0 +1,166 @@
+"""Pins for the oracle's ablation orderings (paper Sec. 6.3, Table 3), attention recall (Eq. 3) and the
+paper's step schedule (Sec. 6.1 implementation details, App. B, App. C)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dfs_oracle as O
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 5])
+def test_hilbert_2d_is_a_hilbert_curve(b):
+    n = 1 << b
+    h, w = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    h, w = h.ravel(), w.ravel()
+    key = O.hilbert_key_nd([h, w], b)
+    assert np.array_equal(np.sort(key), np.arange(4 ** b))
+    order = np.argsort(key)
+    cells = np.stack([h[order], w[order]], axis=1)
+    assert np.all(np.abs(np.diff(cells, axis=0)).sum(axis=1) == 1)
+    assert tuple(cells[0]) == (0, 0) and tuple(cells[-1]) == (n - 1, 0)
+
+
+def _brute_block3d(T, H, W):
+    out = []
+    for ct in range(-(-T // 4)):
+        for ch in range(-(-H // 4)):
+            for cw in range(-(-W // 4)):
+                for t in range(4 * ct, min(4 * ct + 4, T)):
+                    for h in range(4 * ch, min(4 * ch + 4, H)):
+                        for w in range(4 * cw, min(4 * cw + 4, W)):
+                            out.append((t * H + h) * W + w)
+    return np.array(out)
+
+
+@pytest.mark.parametrize("T,H,W", [(4, 8, 8), (3, 5, 7), (6, 9, 10)])
+def test_ablation_orders(T, H, W):
+    N = T * H * W
+    orders = {k: np.argsort(O.order_keys(k, T, H, W), kind="stable") for k in O.ORDERS}
+    for k, order in orders.items():
+        assert np.array_equal(np.sort(order), np.arange(N)), k
+        assert np.unique(O.order_keys(k, T, H, W)).size == N, k
+    assert np.array_equal(orders["raster"], np.arange(N))
+    assert np.array_equal(orders["block3d"], _brute_block3d(T, H, W))
+    # hilbert2d: frame after frame, and inside a frame the 2D Hilbert order restricted to the frame
+    h2 = orders["hilbert2d"]
+    assert np.array_equal(h2 // (H * W), np.repeat(np.arange(T), H * W))
+    b2 = O.cube_bits(1, H, W)
+    for t in range(T):
+        frame = h2[t * H * W:(t + 1) * H * W] - t * H * W
+        key = O.hilbert_key_nd([frame // W, frame % W], b2)
+        assert np.all(np.diff(key) > 0)
+    assert np.array_equal(orders["hilbert3d"], O.hilbert_perm(T, H, W, 0, 16)[0][:N])
+
+
+def test_token_order_layout_matches_hilbert_perm_layout():
+    for kind in O.ORDERS:
+        perm_pad, inv, blk_valid = O.token_order(kind, 3, 5, 7, 9, 16)
+        assert np.array_equal(perm_pad[inv], np.arange(3 * 5 * 7 + 9))
+        assert blk_valid.sum() == 3 * 5 * 7 + 9 and np.all(perm_pad[105:112] == -1)
+        assert np.array_equal(perm_pad[112:121], 105 + np.arange(9))
+    a = O.token_order("hilbert3d", 3, 5, 7, 9, 16)
+    b = O.hilbert_perm(3, 5, 7, 9, 16)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_locality_ranking_of_orders_on_a_smooth_field():
+    """Direction of Table 3 / Table 1 on a synthetic smooth field: locality-aware orders give lower
+    intra-block variance than raster, and the 3D Hilbert order is the best of the four."""
+    T, H, W, B = 8, 16, 16, 64
+    n = np.arange(T * H * W)
+    t, h, w = n // (H * W), (n // W) % H, n % W
+    field = np.stack([np.sin(0.5 * t + 0.3 * h), np.cos(0.4 * h - 0.35 * w), np.sin(0.45 * w + 0.25 * t)], axis=1)
+    var = {}
+    for kind in O.ORDERS:
+        order = np.argsort(O.order_keys(kind, T, H, W), kind="stable")
+        var[kind] = field[order].reshape(-1, B, 3).var(axis=1).mean()
+    # (with B = 64 on a power-of-two grid the 3D Hilbert blocks are exactly the 4x4x4 cubes of block3d)
+    assert var["hilbert3d"] <= var["block3d"] * (1 + 1e-9) and var["block3d"] < var["raster"]
+    assert var["hilbert3d"] < var["hilbert2d"] < var["raster"]
+
+
+# ------------------------------------------------------------------ recall (Eq. 3)
+
+def _setup(seed, M=5, B=4, d=3, heads=2):
+    rng = np.random.default_rng(seed)
+    q, k = (rng.standard_normal((heads, M * B, d)) * 1.5 for _ in range(2))
+    return q, k, M, B, d
+
+
+def test_recall_definition_by_loops():
+    q, k, M, B, d = _setup(0)
+    blk_valid = np.array([4, 4, 4, 4, 2])
+    rng = np.random.default_rng(1)
+    mask = (rng.random((2, M, M)) < 0.5).astype(np.uint8)
+    got = O.attention_recall(q, k, mask, blk_valid, B)
+    real = [p for u in range(M) for p in range(u * B, u * B + blk_valid[u])]
+    for h in range(2):
+        kept_mass = 0.0
+        for i in real:
+            row = [math.exp(float(np.dot(q[h, i], k[h, j])) / math.sqrt(d)) for j in real]
+            z = sum(row)
+            kept_mass += sum(x for x, j in zip(row, real) if mask[h, i // B, j // B]) / z
+        assert abs(got[h] - kept_mass / len(real)) < 1e-12
+
+
+def test_recall_closed_forms():
+    q, k, M, B, d = _setup(2)
+    full = np.full(M, B)
+    assert np.allclose(O.attention_recall(q, k, np.ones((2, M, M), np.uint8), full, B), 1.0)
+    assert np.allclose(O.attention_recall(q, k, np.zeros((2, M, M), np.uint8), full, B), 0.0)
+    # recall is the mean over rows of exp(lse over kept keys - lse over all keys)
+    rng = np.random.default_rng(3)
+    mask = (rng.random((2, M, M)) < 0.6).astype(np.uint8); mask[:, np.arange(M), np.arange(M)] = 1
+    v = np.zeros_like(q)
+    _, lse_s = O.sparse_attn(q, k, v, mask, full, B)
+    _, lse_d = O.sparse_attn(q, k, v, np.ones_like(mask), full, B)
+    np.testing.assert_allclose(O.attention_recall(q, k, mask, full, B), np.exp(lse_s - lse_d).mean(axis=1), rtol=1e-12)
+
+
+def test_true_topk_blocks_recall_at_least_k_over_m():
+    """Selecting, per query block, the K key blocks of largest true mass (Eq. 6) keeps at least K/M of the
+    mass (the step the proof of Corollary 4.5 rests on)."""
+    q, k, M, B, d = _setup(4, M=8)
+    K = 3
+    mask = np.zeros((2, M, M), np.uint8)
+    for h in range(2):
+        s = q[h] @ k[h].T / math.sqrt(d)
+        a = np.exp(s - s.max(axis=1, keepdims=True)); a /= a.sum(axis=1, keepdims=True)
+        alpha = a.reshape(M, B, M, B).sum(axis=(1, 3))
+        for u in range(M):
+            mask[h, u, np.argsort(-alpha[u])[:K]] = 1
+    r = O.attention_recall(q, k, mask, np.full(M, B), B)
+    assert np.all(r >= K / M)
+
+
+# ------------------------------------------------------------------ schedule (Sec. 6.1, App. B, App. C)
+
+def test_paper_schedule_50_steps():
+    T = 50
+    steps = [O.paper_schedule(T, t, cached_keep=None) for t in range(T)]
+    dense = [d for d, _, _ in steps]
+    assert dense == [t <= 12 for t in range(T)]                      # first 25 % of the steps
+    sp = [s for d, _, s in steps if not d]
+    assert sorted(set(round(x, 6) for x in sp)) == [0.7, 0.8, 0.9]   # keep ratio 0.3 -> 0.2 -> 0.1
+    assert sp == sorted(sp)
+    assert abs(np.mean(sp) - 0.8) < 0.005                            # "approximately 80 %" over the remaining steps
+    # walk the schedule with a cache: refresh at the first sparse step, at multiples of delta = 12 and
+    # whenever the budget changed
+    cached, refreshes = None, []
+    for t in range(T):
+        d, refresh, s = O.paper_schedule(T, t, cached_keep=cached)
+        if not d and refresh:
+            refreshes.append(t); cached = 1.0 - s
+    assert refreshes == [13, 24, 25, 36, 38, 48]
+
+
+def test_paper_schedule_four_step_distilled():
+    """App. C: the first step is dense and the mask is recomputed on each of the three following steps."""
+    cached, seen = None, []
+    for t in range(4):
+        d, refresh, s = O.paper_schedule(4, t, cached_keep=cached)
+        seen.append((d, refresh, round(s, 6)))
+        if not d and refresh:
+            cached = 1.0 - s
+    assert seen == [(True, False, 0.0), (False, True, 0.7), (False, True, 0.8), (False, True, 0.9)]
