@@ -71,6 +71,13 @@ typedef struct {
 } dfs_sizes;
 
 typedef enum {
+  DFS_ORDER_HILBERT3D = 0, /* the method's order: 3D Hilbert curve over (t,h,w) (Sec. 5.1) */
+  DFS_ORDER_RASTER = 1,    /* per-frame row-major, the model's own order */
+  DFS_ORDER_HILBERT2D = 2, /* Hilbert order inside each frame, frames in sequence (ablation, Sec. 6.3) */
+  DFS_ORDER_BLOCK3D = 3    /* 4x4x4 cubes in raster order of the cubes, raster inside a cube (ablation, Sec. 6.3) */
+} dfs_order;
+
+typedef enum {
   DFS_WS_HILBERT_PERM = 0,
   DFS_WS_BLOCK_SCORE = 1,
   DFS_WS_SELECT_MASK = 2,
@@ -103,6 +110,13 @@ int32_t dfs_keep_count(double sparsity, int32_t M_v);
  */
 int dfs_hilbert_perm(const dfs_geom* g, int32_t* perm_pad, int32_t* inv, int32_t* blk_valid,
                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Token permutation for any of the traversal orders of the ablation in Sec. 6.3 (Table 3); with
+ * DFS_ORDER_HILBERT3D it is dfs_hilbert_perm.  Same outputs, layout and workspace as dfs_hilbert_perm.
+ */
+int dfs_token_order(const dfs_geom* g, int order, int32_t* perm_pad, int32_t* inv, int32_t* blk_valid,
+                    void* ws, size_t ws_bytes, void* stream);
 
 /*
  * X' = P(X) (Algorithm 1 step 1): x_perm[h, p, :] = x[h, perm_pad[p], :], zeros where
@@ -193,6 +207,25 @@ int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, cons
                 const int32_t* perm_pad, const int32_t* inv, int refresh, int mode, double sparsity,
                 double mass, dfs_mask_state* st, float scale, void* o, void* ws, size_t ws_bytes,
                 void* stream);
+
+/*
+ * Attention recall (Eq. 3): recall[h] = ||A * M||_1 / ||A||_1, the mean over the real query rows of the
+ * attention mass that falls on kept keys, from the log-sum-exp of a run under the mask and of a run with
+ * all blocks kept: per row exp(lse_sparse - lse_dense).  The quality proxy of Sec. 3.2 / Fig. 3.
+ *   lse_sparse, lse_dense [heads, N_pad] in (from dfs_sparse_attn_fwd);  recall [heads] out, fp32.
+ */
+int dfs_recall(const dfs_geom* g, const float* lse_sparse, const float* lse_dense, float* recall, void* stream);
+
+/*
+ * The paper's step schedule (Sec. 6.1 "Implementation details", App. B; Algorithm 1 for the refresh).  Host only.
+ * Steps of the first quarter (t < total_steps/4) run dense attention (*dense = 1).  After that the keep ratio
+ * starts at 0.3 and drops by 0.1 every further quarter (*sparsity = 0.7, 0.8, 0.9: about 80 % on average).
+ * *refresh = 1 when t is a multiple of delta (12 in the paper for 50 steps), when no mask exists yet
+ * (cached_keep < 0) or when the cached mask was built for another keep ratio (cached_keep != 1 - *sparsity);
+ * the last two conditions are readings the paper leaves open.
+ */
+int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_keep, int32_t* dense, int32_t* refresh,
+                 double* sparsity);
 
 #ifdef __cplusplus
 }

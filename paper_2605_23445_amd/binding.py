@@ -64,6 +64,9 @@ def _load():
         "dfs_last_error": (C.c_char_p, []),
         "dfs_keep_count": (i32, [dbl, i32]),
         "dfs_hilbert_perm": (C.c_int, [gp, vp, vp, vp, vp, sz, vp]),
+        "dfs_token_order": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, sz, vp]),
+        "dfs_recall": (C.c_int, [gp, vp, vp, vp, vp]),
+        "dfs_schedule": (C.c_int, [i32, i32, i32, dbl, C.POINTER(i32), C.POINTER(i32), C.POINTER(dbl)]),
         "dfs_permute": (C.c_int, [gp, C.c_int, vp, vp, vp, vp]),
         "dfs_block_score": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, sz, vp]),
         "dfs_select_mask": (C.c_int, [gp, vp, C.c_int, dbl, dbl, vp, vp, vp, i32, vp, vp, sz, vp]),
@@ -80,7 +83,9 @@ def _load():
 
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
-           "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward")
+           "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
+           "dfs_schedule")
+DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
 
 def _check(rc: int):
@@ -139,6 +144,29 @@ def dfs_hilbert_perm(g: Geom, perm_pad, inv, blk_valid, ws):
     _check(_lib.dfs_hilbert_perm(C.byref(g), _ptr(perm_pad, torch.int32, s.N_pad, "perm_pad"),
                                  _ptr(inv, torch.int32, s.N, "inv"), _ptr(blk_valid, torch.int32, s.M, "blk_valid"),
                                  wp, wb, _stream()))
+
+
+def dfs_token_order(g: Geom, order: int, perm_pad, inv, blk_valid, ws):
+    s = dfs_geom_sizes(g)
+    wp, wb = _ws_args(ws)
+    _check(_lib.dfs_token_order(C.byref(g), int(order), _ptr(perm_pad, torch.int32, s.N_pad, "perm_pad"),
+                                _ptr(inv, torch.int32, s.N, "inv"), _ptr(blk_valid, torch.int32, s.M, "blk_valid"),
+                                wp, wb, _stream()))
+
+
+def dfs_recall(g: Geom, lse_sparse, lse_dense, recall):
+    s = dfs_geom_sizes(g)
+    n = g.heads * s.N_pad
+    _check(_lib.dfs_recall(C.byref(g), _ptr(lse_sparse, torch.float32, n, "lse_sparse"), _ptr(lse_dense, torch.float32, n, "lse_dense"),
+                           _ptr(recall, torch.float32, g.heads, "recall"), _stream()))
+
+
+def dfs_schedule(total_steps: int, t: int, delta: int = 12, cached_keep: float | None = None):
+    """(dense, refresh, sparsity) of step t under the paper's schedule; cached_keep None = no mask yet."""
+    dense, refresh, sparsity = C.c_int32(), C.c_int32(), C.c_double()
+    _check(_lib.dfs_schedule(int(total_steps), int(t), int(delta), -1.0 if cached_keep is None else float(cached_keep),
+                             C.byref(dense), C.byref(refresh), C.byref(sparsity)))
+    return bool(dense.value), bool(refresh.value), sparsity.value
 
 
 def dfs_permute(g: Geom, dtype: int, x, perm_pad, x_perm):

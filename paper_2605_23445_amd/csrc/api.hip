@@ -95,7 +95,7 @@ size_t dfs_workspace_bytes(const dfs_geom* g, int kind) {
   dfs_sizes s;
   if (check_geom(g, &s) != DFS_OK) return 0;
   switch (kind) {
-    case DFS_WS_HILBERT_PERM: return ws_hilbert(s);
+    case DFS_WS_HILBERT_PERM: return ws_hilbert(g, s);
     case DFS_WS_BLOCK_SCORE: return ws_block_score(g, s);
     case DFS_WS_SELECT_MASK: return ws_select_mask(g, s);
     case DFS_WS_FORWARD: return forward_layout(g, s, DFS_F32).total;
@@ -133,6 +133,24 @@ int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, cons
                             scale, base + L.op, nullptr, hs)))
     return rc;
   return run_unperm(g, s, dtype, base + L.op, inv, o, hs);
+}
+
+int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_keep, int32_t* dense, int32_t* refresh,
+                 double* sparsity) {
+  if (!dense || !refresh || !sparsity) return fail(DFS_EINVAL, "dfs_schedule: NULL output");
+  if (total_steps < 1 || t < 0 || t >= total_steps || delta < 1)
+    return fail(DFS_EINVAL, "dfs_schedule: need 0 <= t < total_steps and delta >= 1 (got t=%d, total=%d, delta=%d)", t, total_steps, delta);
+  int quarter = int(floor(double(t) / (0.25 * double(total_steps)) + 1e-9));
+  if (quarter > 3) quarter = 3;
+  if (quarter == 0) {
+    *dense = 1; *refresh = 0; *sparsity = 0.0;
+    return DFS_OK;
+  }
+  const double keep = 0.3 - 0.1 * double(quarter - 1);
+  *dense = 0;
+  *sparsity = 1.0 - keep;
+  *refresh = (t % delta == 0) || cached_keep < 0.0 || fabs(cached_keep - keep) > 1e-12;
+  return DFS_OK;
 }
 
 }  // extern "C"

@@ -33,7 +33,7 @@ int run_unperm(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* o_p
                hipStream_t st);
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s);
 size_t ws_select_mask(const dfs_geom* g, const dfs_sizes& s);
-size_t ws_hilbert(const dfs_sizes& s);
+size_t ws_hilbert(const dfs_geom* g, const dfs_sizes& s);
 
 // bf16 <-> fp32 on raw bits (round to nearest even on the way down)
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }

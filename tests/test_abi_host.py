@@ -88,3 +88,16 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros((2, 256, 64))
     with pytest.raises(ValueError):
         P.dfs_permute(g, P.DFS_F32, x, torch.zeros(256, dtype=torch.int32), x.clone())
+
+
+def test_schedule_matches_oracle_and_rejects_bad_steps():
+    for total in (4, 7, 13, 50, 100):
+        for delta in (1, 3, 12):
+            for t in range(total):
+                for cached in (None, 0.3, 0.2, 0.1):
+                    got = P.dfs_schedule(total, t, delta, cached)
+                    want = O.paper_schedule(total, t, delta, cached_keep=cached)
+                    assert (got[0], got[1], round(got[2], 9)) == (want[0], want[1], round(want[2], 9))
+    for bad in ((0, 0, 1), (10, 10, 1), (10, -1, 1), (10, 3, 0)):
+        with pytest.raises(P.DfsError):
+            P.dfs_schedule(*bad)

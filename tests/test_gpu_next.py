@@ -1,0 +1,111 @@
+"""GPU parity of the rows beyond the core path: the ablation orderings of Sec. 6.3 (bit-exact against the
+oracle), attention recall of Eq. 3 (against the oracle's definition), and a run of the paper's step
+schedule (Sec. 6.1) through the one-call entry point."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dfs_oracle as O
+from workloads import Workload, derived_sizes, make_qkv
+from workloads.synth import as_f64
+
+pytestmark = pytest.mark.gpu
+
+P = pytest.importorskip("paper_2605_23445_amd")
+from tests import gpu_util as G  # noqa: E402
+
+ORDER_ID = {"hilbert3d": P.DFS_ORDER_HILBERT3D, "raster": P.DFS_ORDER_RASTER, "hilbert2d": P.DFS_ORDER_HILBERT2D,
+            "block3d": P.DFS_ORDER_BLOCK3D}
+
+
+@pytest.mark.parametrize("kind", list(ORDER_ID))
+@pytest.mark.parametrize("T,H,W,n_text,B", [(4, 8, 8, 0, 64), (13, 30, 45, 0, 128), (33, 45, 80, 256, 128), (3, 5, 7, 9, 64),
+                                            (1, 1, 1, 0, 64), (9, 2, 130, 1, 128)])
+def test_token_orders_bit_exact(kind, T, H, W, n_text, B):
+    print(f"order {kind} {T}x{H}x{W}+{n_text}", flush=True)
+    g = P.Geom(T, H, W, n_text, 1, 64, B, B)
+    s = P.dfs_geom_sizes(g)
+    perm_pad = torch.full((s.N_pad,), -7, dtype=torch.int32, device="cuda")
+    inv = torch.full((s.N,), -7, dtype=torch.int32, device="cuda")
+    blk_valid = torch.full((s.M,), -7, dtype=torch.int32, device="cuda")
+    ws = G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_HILBERT_PERM))
+    P.dfs_token_order(g, ORDER_ID[kind], perm_pad, inv, blk_valid, ws)
+    want = O.token_order(kind, T, H, W, n_text, B)
+    for got, exp in zip((perm_pad, inv, blk_valid), want):
+        assert np.array_equal(got.cpu().numpy(), exp)
+
+
+def test_recall_against_the_definition():
+    w = Workload("recall_mid", 4, 10, 12, heads=3, d=128, dtype="bf16", B=128, Bs=32, sparsity=(0.5,), seed=31, n_text=20)
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, blk_valid_d = G.gpu_perm(g)
+    blk_valid = blk_valid_d.cpu().numpy()
+    qp, kp, vp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k, v))
+    score = G.gpu_score(g, dt, qp, kp)
+    dense = G.gpu_select(g, score, P.DFS_SELECT_TOPK, 0.0)
+    _, lse_d = G.gpu_attn(g, dt, qp, kp, vp, dense)
+    recall = torch.empty(w.heads, dtype=torch.float32, device="cuda")
+    P.dfs_recall(g, lse_d, lse_d, recall)
+    assert np.allclose(recall.cpu().numpy(), 1.0, atol=1e-6)
+    prev = None
+    for sp in (0.25, 0.5, 0.75):
+        st = G.gpu_select(g, score, P.DFS_SELECT_TOPK, sp)
+        _, lse_s = G.gpu_attn(g, dt, qp, kp, vp, st)
+        P.dfs_recall(g, lse_s, lse_d, recall)
+        got = recall.cpu().numpy()
+        want = O.attention_recall(G.as_f64_dev(qp), G.as_f64_dev(kp), st.mask.cpu().numpy(), blk_valid, w.B)
+        print(f"  sparsity {sp}: recall {got} oracle {want}", flush=True)
+        assert np.abs(got - want).max() <= 5e-3                  # lse of the bf16 kernel is good to 2^-9 relative
+        assert np.all(got > 1.0 - sp)                            # kept blocks hold more than their share
+        if prev is not None:
+            assert np.all(got <= prev + 1e-3)                    # fewer kept blocks, less mass
+        prev = got
+
+
+def test_paper_schedule_run():
+    """A short sampling run under the paper's schedule: dense first quarter, then keep 0.3 / 0.2 / 0.1 with the
+    mask refreshed when the schedule says so; every step's output is checked against the oracle under the mask
+    in force."""
+    w = Workload("sched_mid", 4, 8, 16, heads=2, d=64, dtype="bf16", B=128, Bs=32, sparsity=(0.7,), seed=41)
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, blk_valid_d = G.gpu_perm(g)
+    blk_valid = blk_valid_d.cpu().numpy()
+    inv_np = inv.cpu().numpy()
+    qd, kd, vd = (G.to_dev(x) for x in (q, k, v))
+    K_max = sz["M"]
+    st = P.MaskState(torch.zeros((w.heads, sz["M"], K_max), dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"]), dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"], sz["M"]), dtype=torch.uint8, device="cuda"), None, K_max)
+    ws = G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_FORWARD_BF16))
+    o = torch.empty_like(qd)
+    total, delta, cached, log = 8, 3, None, []
+    for t in range(total):
+        dense, refresh, sp = P.dfs_schedule(total, t, delta, cached)
+        assert (dense, refresh, round(sp, 9)) == tuple(round(x, 9) if isinstance(x, float) else x for x in O.paper_schedule(total, t, delta, cached_keep=cached))
+        kd = torch.roll(kd, 1, dims=1).contiguous()              # the inputs change every step
+        if dense:
+            # dense bypass: all blocks kept; the cached sparse mask (none yet) is left alone
+            all_st = P.MaskState(torch.zeros_like(st.kv_idx), torch.zeros_like(st.kv_cnt), torch.zeros_like(st.mask), None, K_max)
+            P.dfs_forward(g, dt, qd, kd, vd, perm_pad, inv, True, P.DFS_SELECT_TOPK, 0.0, 0.0, all_st, 1 / math.sqrt(w.d), o, ws)
+            mask = all_st.mask.cpu().numpy()
+        else:
+            P.dfs_forward(g, dt, qd, kd, vd, perm_pad, inv, refresh, P.DFS_SELECT_TOPK, sp, 0.0, st, 1 / math.sqrt(w.d), o, ws)
+            if refresh:
+                cached = 1.0 - sp
+            mask = st.mask.cpu().numpy()
+            assert np.all(mask[:, :sz["M_v"], :sz["M_v"]].sum(axis=2) == P.dfs_keep_count(1.0 - cached, sz["M_v"]))
+        log.append((dense, refresh, round(sp, 3)))
+        kp = G.gpu_permute(g, dt, kd, perm_pad); qp = G.gpu_permute(g, dt, qd, perm_pad); vp = G.gpu_permute(g, dt, vd, perm_pad)
+        want, _ = O.sparse_attn(G.as_f64_dev(qp), G.as_f64_dev(kp), G.as_f64_dev(vp), mask, blk_valid, w.B)
+        err = np.abs(G.as_f64_dev(o) - O.unpermute(want, inv_np))
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3
+    print("  schedule:", log, flush=True)
+    assert [d for d, _, _ in log] == [True, True, False, False, False, False, False, False]
+    assert [s for _, _, s in log[2:]] == [0.7, 0.7, 0.8, 0.8, 0.9, 0.9]
+    assert [r for _, r, _ in log[2:]] == [True, True, True, False, True, False]
