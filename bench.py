@@ -88,7 +88,8 @@ def main():
                      dtype=torch.uint8, device="cuda")
     scale = 1.0 / math.sqrt(w.d)
 
-    stages = ["perm_index", "permute_qkv", "block_score", "select_mask", "sparse_attn", "unperm"]
+    fused = w.dtype == "bf16"     # Q gathered / O scattered inside scoring and attention: only K, V are reordered
+    stages = ["perm_index", "permute", "block_score", "select_mask", "sparse_attn", "unperm"]
     n_ev = a.steps * (len(stages) + 1)
     events = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
 
@@ -98,13 +99,21 @@ def main():
                 evs[i].record()
         mark(0)
         P.dfs_hilbert_perm(g, perm_pad, inv, blk_valid, ws); mark(1)
-        P.dfs_permute(g, dt, qd, perm_pad, qp)
+        if not fused:
+            P.dfs_permute(g, dt, qd, perm_pad, qp)
         P.dfs_permute(g, dt, kd, perm_pad, kp)
         P.dfs_permute(g, dt, vd, perm_pad, vp); mark(2)
-        P.dfs_block_score(g, dt, qp, kp, score, ws); mark(3)
+        if fused:
+            P.dfs_block_score_src(g, dt, qd, perm_pad, kp, score, ws); mark(3)
+        else:
+            P.dfs_block_score(g, dt, qp, kp, score, ws); mark(3)
         P.dfs_select_mask(g, score, P.DFS_SELECT_TOPK, a.sparsity, 0.0, None, kv_idx, kv_cnt, K_max, None, ws); mark(4)
-        P.dfs_sparse_attn_fwd(g, dt, qp, kp, vp, kv_idx, kv_cnt, K_max, scale, op, None); mark(5)
-        P.dfs_unperm(g, dt, op, inv, o); mark(6)
+        if fused:
+            P.dfs_sparse_attn_fwd_src(g, dt, qd, perm_pad, kp, vp, kv_idx, kv_cnt, K_max, scale, o, None); mark(5)
+            mark(6)
+        else:
+            P.dfs_sparse_attn_fwd(g, dt, qp, kp, vp, kv_idx, kv_cnt, K_max, scale, op, None); mark(5)
+            P.dfs_unperm(g, dt, op, inv, o); mark(6)
 
     if a.calib_copy:       # a copy of known size: 1 GiB read + 1 GiB written
         src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
@@ -130,7 +139,8 @@ def main():
     flop_dense = 4.0 * float(sz["N"]) ** 2 * w.d * w.heads
     attn_ms = stage_ms["sparse_attn"]
     e = 2 if w.dtype == "bf16" else 4
-    bytes_permute = 3 * w.heads * (sz["N"] + N_pad) * w.d * e + 3 * N_pad * 4
+    n_perm = 2 if fused else 3
+    bytes_permute = n_perm * w.heads * (sz["N"] + N_pad) * w.d * e + n_perm * N_pad * 4
     bytes_unperm = 2 * w.heads * sz["N"] * w.d * e + sz["N"] * 4
     if a.traffic_kib is not None:
         rec = (a.traffic_kib[0] * 1024, a.traffic_kib[1] * 1024)
@@ -155,8 +165,8 @@ def main():
         "attn_dense_equiv_tflops": flop_dense / (attn_ms * 1e-3) / 1e12,
         "mfma_util_pct": 100.0 * flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "stage_ms": {k2: round(v2, 4) for k2, v2 in stage_ms.items()},
-        "permute_gbs": bytes_permute / (stage_ms["permute_qkv"] * 1e-3) / 1e9,
-        "unperm_gbs": bytes_unperm / (stage_ms["unperm"] * 1e-3) / 1e9,
+        "permute_gbs": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9,
+        "unperm_gbs": None if fused else bytes_unperm / (stage_ms["unperm"] * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
                      "achieved": flop_exec / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

@@ -130,7 +130,8 @@ int dfs_permute(const dfs_geom* g, int dtype, const void* x, const int32_t* perm
  * average-pooled over sub-blocks of Bs rows (mean over real rows; a sub-block without real
  * rows is empty), A_hat = row-softmax(Q_hat K_hat^T / sqrt(d)) over the non-empty video
  * sub-blocks, and score[h,u,v] = sum of the r x r entries of A_hat in block pair (u,v).
- * Text blocks are not scored.  Arithmetic is fp32.
+ * Text blocks are not scored.  Means, softmax and sums are fp32; the logits run on the bf16 matrix cores
+ * over an exact three-term split of the fp32 means (as accurate as an fp32 contraction).
  *   q_perm, k_perm [heads, N_pad, d] in (`dtype`);  score [heads, M_v, M_v] out, fp32.
  * ws: DFS_WS_BLOCK_SCORE.
  */
@@ -177,6 +178,20 @@ int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double spar
 int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
                         const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max,
                         float scale, void* o_perm, float* lse, void* stream);
+
+/*
+ * Variants that read Q, and write O, in SOURCE order through the permutation, so that Q' and O' are never
+ * materialised (only K and V take a reorder pass): the query rows are gathered where they are consumed and the
+ * attention kernel scatters its output rows.  Results are bit-identical to dfs_permute + the plain call
+ * (+ dfs_unperm).  bf16 tensors only.
+ *   q [heads, N, d] in, source order;  perm_pad [N_pad] from dfs_hilbert_perm;  o [heads, N, d] out, source order
+ *   lse [heads, N_pad] out or NULL, indexed by reordered position as in dfs_sparse_attn_fwd.
+ */
+int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
+                        float* score, void* ws, size_t ws_bytes, void* stream);
+int dfs_sparse_attn_fwd_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
+                            const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale,
+                            void* o, float* lse, void* stream);
 
 /*
  * O = P^{-1}(O') (Algorithm 1 step 3, last line): o[h, n, :] = o_perm[h, inv[n], :].

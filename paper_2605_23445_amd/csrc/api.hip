@@ -119,20 +119,27 @@ int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, cons
     return fail(DFS_EWORKSPACE, "dfs_forward: workspace of %zu bytes needed (256-byte aligned), got %zu", L.total, ws_bytes);
   char* base = static_cast<char*>(ws);
   hipStream_t hs = as_stream(stream);
-  if ((rc = run_permute(g, s, dtype, q, perm_pad, base + L.qp, hs))) return rc;
+  // bf16: Q is gathered where it is consumed (pooling, attention) and O is scattered by the attention kernel,
+  // so only K and V take a reorder pass.  fp32 (small problems): every tensor is reordered.
+  const bool fused = dtype == DFS_BF16;
+  const int32_t* index = fused ? perm_pad : nullptr;
+  const void* q_in = fused ? q : base + L.qp;
+  void* o_out = fused ? o : base + L.op;
+  if (!fused && (rc = run_permute(g, s, dtype, q, perm_pad, base + L.qp, hs))) return rc;
   if ((rc = run_permute(g, s, dtype, k, perm_pad, base + L.kp, hs))) return rc;
   if ((rc = run_permute(g, s, dtype, v, perm_pad, base + L.vp, hs))) return rc;
   if (refresh) {
     float* score = reinterpret_cast<float*>(base + L.score);
-    if ((rc = run_block_score(g, s, dtype, base + L.qp, base + L.kp, score, base + L.sub, hs))) return rc;
+    if ((rc = run_block_score(g, s, dtype, q_in, base + L.kp, score, base + L.sub, index, hs))) return rc;
     if ((rc = run_select_mask(g, s, score, mode, sparsity, mass, st->mask, st->kv_idx, st->kv_cnt, st->K_max,
                               st->k_head, base + L.sub, hs)))
       return rc;
   }
-  if ((rc = run_sparse_attn(g, s, dtype, base + L.qp, base + L.kp, base + L.vp, st->kv_idx, st->kv_cnt, st->K_max,
-                            scale, base + L.op, nullptr, hs)))
+  if ((rc = run_sparse_attn(g, s, dtype, q_in, base + L.kp, base + L.vp, st->kv_idx, st->kv_cnt, st->K_max, scale, o_out,
+                            nullptr, index, hs)))
     return rc;
-  return run_unperm(g, s, dtype, base + L.op, inv, o, hs);
+  if (!fused) return run_unperm(g, s, dtype, base + L.op, inv, o, hs);
+  return DFS_OK;
 }
 
 int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_keep, int32_t* dense, int32_t* refresh,

@@ -56,8 +56,8 @@ template <int D, int BM, int QT>
 __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_eu(2 / QT, 2 / QT)))
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int32_t* __restrict__ kv_idx, const int32_t* __restrict__ kv_cnt, int K_max, uint16_t* __restrict__ o,
-                 float* __restrict__ lse, int64_t N_pad, int64_t N_v, int n_text, int M_v, int M, int total_wg,
-                 int wg_per_xcd, int head_major, float scale) {
+                 float* __restrict__ lse, const int32_t* __restrict__ row_index, int64_t N_src, int64_t N_pad, int64_t N_v, int n_text,
+                 int M_v, int M, int total_wg, int wg_per_xcd, int head_major, float scale) {
   constexpr int NW = BM / (32 * QT);               // waves: one per 32 QT query rows
   constexpr int CH = D / 8;                        // 16-byte chunks per row
   constexpr int TILE = KN * D;                     // elements per tile
@@ -96,13 +96,25 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   const uint16_t* vh = v + head_off;
   const int64_t q_row0 = int64_t(u) * BM + wave * (32 * QT) + n;      // query tile a adds 32 a
 
+  // Where this lane's query rows live.  With row_index (the permutation) Q is read from, and O written to,
+  // the tensors in source order, which spares the reorder passes of Q and O; -1 marks a pad row.
+  int64_t io_row[QT];
+#pragma unroll
+  for (int a = 0; a < QT; ++a) {
+    const int64_t pos = q_row0 + 32 * a;
+    io_row[a] = row_index ? int64_t(row_index[pos]) : pos;
+    if (row_index && io_row[a] >= N_src) io_row[a] = -1;
+  }
+  const int64_t io_off = int64_t(head) * (row_index ? N_src : N_pad) * D;
+
   // Q rows as the B operand of S^T = K Q^T: lane (n, h) holds Q[row][16 kk + 8 h .. + 7]
   bf16x8 qf[QT][D / 16];
 #pragma unroll
   for (int a = 0; a < QT; ++a) {
-    const u32x4* qp = reinterpret_cast<const u32x4*>(q + head_off + (q_row0 + 32 * a) * D);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(q + io_off + (io_row[a] < 0 ? 0 : io_row[a]) * D);
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) qf[a][kk] = __builtin_bit_cast(bf16x8, qp[2 * kk + h]);
+    for (int kk = 0; kk < D / 16; ++kk)
+      qf[a][kk] = __builtin_bit_cast(bf16x8, io_row[a] < 0 ? u32x4{0u, 0u, 0u, 0u} : qp[2 * kk + h]);
   }
 
   f32x16 oacc[QT][D / 32];
@@ -392,16 +404,18 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   for (int a = 0; a < QT; ++a) {
     const float l_tot = l_run[a] + __shfl_xor(l_run[a], 32, 64);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    uint16_t* orow = o + head_off + (q_row0 + 32 * a) * D;
+    uint16_t* orow = o + io_off + (io_row[a] < 0 ? 0 : io_row[a]) * D;
+    if (io_row[a] >= 0) {
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        bf16x4 w;
+        for (int j = 0; j < 4; ++j) {
+          bf16x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[a][dt][4 * j + e] * inv);
-        *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * j + 4 * h) = __builtin_bit_cast(u32x2, w);
-      }
+          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[a][dt][4 * j + e] * inv);
+          *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * j + 4 * h) = __builtin_bit_cast(u32x2, w);
+        }
+    }
     if (lse && h == 0)
       lse[int64_t(head) * N_pad + q_row0 + 32 * a] =
           l_tot > 0.f ? (m_run[a] * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
@@ -491,7 +505,7 @@ __global__ void __launch_bounds__(128) attn_f32_kernel(const float* __restrict__
 
 int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q, const void* k, const void* v,
                     const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale, void* o, float* lse,
-                    hipStream_t st) {
+                    const int32_t* row_index, hipStream_t st) {
   if (K_max < 1) return fail(DFS_ESHAPE, "dfs_sparse_attn_fwd: K_max=%d must be positive", K_max);
   if (dtype == DFS_BF16) {
     const int64_t total = int64_t(g->heads) * s.M;
@@ -502,12 +516,13 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
 #define ATTN(DD, BB, QQ)                                                                                                    \
   attn_bf16_kernel<DD, BB, QQ><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
                                                              static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
-                                                             static_cast<uint16_t*>(o), lse, s.N_pad, s.N_v, g->n_text,       \
-                                                             s.M_v, s.M, int(total), per_xcd, head_major, scale)
+                                                             static_cast<uint16_t*>(o), lse, row_index, s.N, s.N_pad, s.N_v,  \
+                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, head_major, scale)
     if (g->d == 64) { if (g->B == 64) ATTN(64, 64, 1); else ATTN(64, 128, 1); }
     else            { if (g->B == 64) ATTN(128, 64, 1); else ATTN(128, 128, 1); }
 #undef ATTN
   } else {
+    if (row_index) return fail(DFS_EDTYPE, "dfs_sparse_attn_fwd: reading Q / writing O through the permutation needs bf16 tensors");
     if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
     dim3 grid(unsigned(s.M), unsigned(g->heads));
     if (g->d == 64)
@@ -535,5 +550,17 @@ extern "C" int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_p
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!q_perm || !k_perm || !v_perm || !kv_idx || !kv_cnt || !o_perm) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd: NULL argument");
   if (!(scale > 0.f)) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd: scale must be positive");
-  return run_sparse_attn(g, s, dtype, q_perm, k_perm, v_perm, kv_idx, kv_cnt, K_max, scale, o_perm, lse, as_stream(stream));
+  return run_sparse_attn(g, s, dtype, q_perm, k_perm, v_perm, kv_idx, kv_cnt, K_max, scale, o_perm, lse, nullptr, as_stream(stream));
+}
+
+extern "C" int dfs_sparse_attn_fwd_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
+                                       const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale,
+                                       void* o, float* lse, void* stream) {
+  dfs_sizes s;
+  int rc = check_geom(g, &s);
+  if (rc) return rc;
+  if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_sparse_attn_fwd_src: bf16 tensors only");
+  if (!q || !perm_pad || !k_perm || !v_perm || !kv_idx || !kv_cnt || !o) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd_src: NULL argument");
+  if (!(scale > 0.f)) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd_src: scale must be positive");
+  return run_sparse_attn(g, s, dtype, q, k_perm, v_perm, kv_idx, kv_cnt, K_max, scale, o, lse, perm_pad, as_stream(stream));
 }

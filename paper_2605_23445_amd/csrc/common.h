@@ -21,14 +21,15 @@ inline int elem_size(int dtype) { return dtype == DFS_BF16 ? 2 : 4; }
 // Stage entry points without argument checks, used by dfs_forward after it has validated once.
 int run_permute(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* x, const int32_t* perm_pad,
                 void* x_perm, hipStream_t st);
+// q_index (may be NULL): the permutation; Q is then read in source order and gathered while pooling.
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm,
-                    float* score, void* ws, hipStream_t st);
+                    float* score, void* ws, const int32_t* q_index, hipStream_t st);
 int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, int mode, double sparsity,
                     double mass, uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max,
                     int32_t* k_head, void* ws, hipStream_t st);
 int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q, const void* k, const void* v,
                     const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale, void* o, float* lse,
-                    hipStream_t st);
+                    const int32_t* row_index, hipStream_t st);   // row_index (may be NULL, bf16 only): Q and O in source order
 int run_unperm(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* o_perm, const int32_t* inv, void* o,
                hipStream_t st);
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s);

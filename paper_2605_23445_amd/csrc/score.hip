@@ -38,8 +38,9 @@ __device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uin
 // Output row layout: [3][D] bf16 (hi, mid, lo planes).
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_perm, const void* __restrict__ k_perm,
-                                                   uint16_t* __restrict__ q_hat, uint16_t* __restrict__ k_hat, int64_t N_pad,
-                                                   int64_t N_v, int Bs, int M_s, float q_scale) {
+                                                   uint16_t* __restrict__ q_hat, uint16_t* __restrict__ k_hat,
+                                                   const int32_t* __restrict__ q_index, int64_t N_src, int64_t N_pad, int64_t N_v, int Bs,
+                                                   int M_s, float q_scale) {
   constexpr int EPL = BF16 ? 8 : 4;           // elements per lane (16 bytes)
   constexpr int TPR = D / EPL;                // lanes per row
   constexpr int RPP = 64 / TPR;               // rows per pass
@@ -56,9 +57,17 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
   float acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-  const u32x4* base = reinterpret_cast<const u32x4*>(src) + (int64_t(head) * N_pad + row0) * TPR + c;
+  // With q_index (the permutation) the query rows are gathered from the tensor in source order, which spares
+  // the reorder pass of Q.
+  const bool gather = blockIdx.z == 0 && q_index != nullptr;
+  const u32x4* base = reinterpret_cast<const u32x4*>(src) + (gather ? int64_t(head) * N_src * TPR : (int64_t(head) * N_pad + row0) * TPR) + c;
   for (int i = rg; i < cnt; i += RPP) {
-    const u32x4 v = __builtin_nontemporal_load(base + int64_t(i) * TPR);
+    int64_t from = i;
+    if (gather) {
+      from = q_index[row0 + i];
+      if (from < 0 || from >= N_src) continue;
+    }
+    const u32x4 v = __builtin_nontemporal_load(base + from * TPR);
     if (BF16) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -246,7 +255,7 @@ size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s) {
 }
 
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm, float* score,
-                    void* ws, hipStream_t st) {
+                    void* ws, const int32_t* q_index, hipStream_t st) {
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
   const size_t half = align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t));
   uint16_t* q_hat = static_cast<uint16_t*>(ws);
@@ -254,7 +263,7 @@ int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   dim3 pg(unsigned((s.M_s + 3) / 4), unsigned(g->heads), 2);
   const bool bf = dtype == DFS_BF16;
   const float scale = 1.0f / sqrtf(float(g->d));
-#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
+#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_index, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
   if (g->d == 64) { if (bf) POOL(true, 64); else POOL(false, 64); }
   else            { if (bf) POOL(true, 128); else POOL(false, 128); }
 #undef POOL
@@ -279,5 +288,18 @@ extern "C" int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm,
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
     return fail(DFS_EWORKSPACE, "dfs_block_score: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
-  return run_block_score(g, s, dtype, q_perm, k_perm, score, ws, as_stream(stream));
+  return run_block_score(g, s, dtype, q_perm, k_perm, score, ws, nullptr, as_stream(stream));
+}
+
+extern "C" int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
+                                   float* score, void* ws, size_t ws_bytes, void* stream) {
+  dfs_sizes s;
+  int rc = check_geom(g, &s);
+  if (rc) return rc;
+  if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_block_score_src: bf16 tensors only");
+  if (!q || !perm_pad || !k_perm || !score) return fail(DFS_EINVAL, "dfs_block_score_src: NULL argument");
+  const size_t need = ws_block_score(g, s);
+  if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
+    return fail(DFS_EWORKSPACE, "dfs_block_score_src: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
+  return run_block_score(g, s, dtype, q, k_perm, score, ws, perm_pad, as_stream(stream));
 }

@@ -361,3 +361,29 @@ def test_full_size_workloads(name, oracle_heads):
         loose = _check_p3(np.stack([score64[h] for h in oracle_heads]), mask[list(oracle_heads)], kk, sz["M_v"], SCORE_TOL * sz["r"])
         say(f"  sparsity {sp}: k={kk}, masks bit-exact on GPU scores; rows at the fp64 threshold: {loose}")
         _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, blocks, heads_idx=list(oracle_heads))
+
+
+@pytest.mark.parametrize("w", [MID_BF16, MID_D64, MID_B64], ids=lambda w: w.name)
+def test_source_order_variants_are_bit_identical(w):
+    """dfs_block_score_src / dfs_sparse_attn_fwd_src (Q gathered, O scattered through the permutation) give the
+    same bits as reorder + plain call + inverse reorder."""
+    say(f"source-order variants {w.name}")
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    qd, kd, vd = (G.to_dev(x) for x in (q, k, v))
+    qp, kp, vp = (G.gpu_permute(g, dt, x, perm_pad) for x in (qd, kd, vd))
+    score = G.gpu_score(g, dt, qp, kp)
+    score2 = torch.full_like(score, float("nan"))
+    P.dfs_block_score_src(g, dt, qd, perm_pad, kp, score2, G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_BLOCK_SCORE)))
+    assert torch.equal(score.view(torch.int32), score2.view(torch.int32))
+    st = G.gpu_select(g, score, P.DFS_SELECT_TOPK, w.sparsity[0])
+    o_perm, lse = G.gpu_attn(g, dt, qp, kp, vp, st)
+    o_ref = G.gpu_unperm(g, dt, o_perm, inv)
+    o2 = torch.full_like(qd, float("nan"))
+    lse2 = torch.full_like(lse, float("nan"))
+    P.dfs_sparse_attn_fwd_src(g, dt, qd, perm_pad, kp, vp, st.kv_idx, st.kv_cnt, st.K_max, 1.0 / math.sqrt(w.d), o2, lse2)
+    assert torch.equal(o_ref.view(torch.int16), o2.view(torch.int16))
+    real = (perm_pad >= 0)
+    assert torch.equal(lse[:, real].view(torch.int32), lse2[:, real].view(torch.int32))
