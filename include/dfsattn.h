@@ -44,7 +44,8 @@ typedef enum { DFS_F32 = 0, DFS_BF16 = 1 } dfs_dtype;
 
 typedef enum {
   DFS_SELECT_TOPK = 0,     /* Eq. 9: every query block keeps ceil((1-sparsity)*M_v) key blocks */
-  DFS_SELECT_MASS_HEAD = 1 /* per-head keep count from the cumulative score mass (see dfs_select_mask) */
+  DFS_SELECT_MASS_HEAD = 1, /* per-head keep count from the cumulative score mass (see dfs_select_mask) */
+  DFS_SELECT_MASS_ROW = 2   /* per-row keep count from the cumulative score mass */
 } dfs_select_mode;
 
 /* Problem geometry (Algorithm 1 inputs; Sec. 3.1 for the token layout). */
@@ -148,6 +149,8 @@ int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm, const void
  *     k_h = max(ceil(mean_u k_u), dfs_keep_count(sparsity, M_v)) with `sparsity` the cap; k_h is
  *     clamped to K_max - M_x.  (This rule is the benchmark's adaptive ratio, not the step
  *     schedule of Sec. 5.3, which is a host policy on `sparsity`.)
+ *   DFS_SELECT_MASS_ROW:  every row keeps its own max(k_u, dfs_keep_count(sparsity, M_v)) blocks, clamped to
+ *     K_max - M_x; k_head is not written.
  * Text: video query blocks also keep all M_x text key blocks; text query blocks keep all M.
  *   score  [heads, M_v, M_v] in
  *   mask   [heads, M, M] out, uint8 0/1, may be NULL
@@ -155,7 +158,7 @@ int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm, const void
  *          beyond the count are unspecified; rows that keep all M blocks are not written
  *   kv_cnt [heads, M] out: number of kept key blocks
  *   k_head [heads] out, may be NULL: the k used for each head
- *   K_max >= k + M_x (TOPK), >= dfs_keep_count(cap) + M_x (MASS_HEAD)
+ *   K_max >= k + M_x (TOPK), >= dfs_keep_count(cap) + M_x (MASS_HEAD, MASS_ROW)
  * ws: DFS_WS_SELECT_MASK.
  */
 int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double sparsity, double mass,

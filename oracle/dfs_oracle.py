@@ -317,6 +317,22 @@ def select_mass_head(score: np.ndarray, mass: float, cap_sparsity: float, M_x: i
     return mask, k_head
 
 
+def select_mass_row(score: np.ndarray, mass: float, cap_sparsity: float, M_x: int = 0):
+    """Adaptive per-row ratio: every query block keeps its own mass_keep_count blocks, never fewer than the
+    keep count at the sparsity cap.  (The per-row form of select_mass_head.)  Returns (mask, k_row [heads, M_v])."""
+    heads, M_v, _ = score.shape
+    k_floor = keep_count(cap_sparsity, M_v)
+    mask = np.empty((heads, M_v + M_x, M_v + M_x), dtype=np.uint8)
+    k_row = np.empty((heads, M_v), dtype=np.int32)
+    for h in range(heads):
+        cols = []
+        for u in range(M_v):
+            k_row[h, u] = max(mass_keep_count(score[h, u], mass), k_floor)
+            cols.append(_rank_order(score[h, u])[:k_row[h, u]])
+        mask[h] = build_mask(cols, M_v, M_x)
+    return mask, k_row
+
+
 def mask_to_lists(mask: np.ndarray, K_max: int):
     """kv_idx [heads, M, K_max] (ascending kept columns, -1 beyond the count) and kv_cnt.
     A row that keeps all M blocks needs no list; it is listed only if K_max has room for it."""

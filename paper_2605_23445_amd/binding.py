@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdfsattn.so")
 
 DFS_F32, DFS_BF16 = 0, 1
-DFS_SELECT_TOPK, DFS_SELECT_MASS_HEAD = 0, 1
+DFS_SELECT_TOPK, DFS_SELECT_MASS_HEAD, DFS_SELECT_MASS_ROW = 0, 1, 2
 DFS_WS_HILBERT_PERM, DFS_WS_BLOCK_SCORE, DFS_WS_SELECT_MASK, DFS_WS_FORWARD, DFS_WS_FORWARD_BF16 = 0, 1, 2, 3, 4
 
 

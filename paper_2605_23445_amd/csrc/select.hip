@@ -107,9 +107,10 @@ __global__ void __launch_bounds__(256) head_count_kernel(const int32_t* __restri
   }
 }
 
-// Top-k of one row.  k is `k_fixed` or, when k_per_head is given, k_per_head[head].
+// Top-k of one row.  k is `k_fixed`, or k_per_head[head], or clamp(k_per_row[head, u], k_fixed, k_cap).
 __global__ void __launch_bounds__(64) select_kernel(const float* __restrict__ score, int M_v, int M_x, int k_fixed,
-                                                    const int32_t* __restrict__ k_per_head, uint8_t* __restrict__ mask,
+                                                    const int32_t* __restrict__ k_per_head, const int32_t* __restrict__ k_per_row,
+                                                    int k_cap, uint8_t* __restrict__ mask,
                                                     int32_t* __restrict__ kv_idx, int32_t* __restrict__ kv_cnt, int K_max,
                                                     int32_t* __restrict__ k_head_out) {
   extern __shared__ uint32_t keys[];
@@ -123,8 +124,12 @@ __global__ void __launch_bounds__(64) select_kernel(const float* __restrict__ sc
     if (lane == 0) kv_cnt[int64_t(head) * M + u] = M;
     return;
   }
-  const int k = k_per_head ? k_per_head[head] : k_fixed;
-  if (k_head_out && !k_per_head && u == 0 && lane == 0) k_head_out[head] = k;
+  int k = k_per_head ? k_per_head[head] : k_fixed;
+  if (k_per_row) {
+    const int ku = k_per_row[int64_t(head) * M_v + u];
+    k = ku < k_fixed ? k_fixed : (ku > k_cap ? k_cap : ku);
+  }
+  if (k_head_out && !k_per_head && !k_per_row && u == 0 && lane == 0) k_head_out[head] = k;
   const float* row = score + (int64_t(head) * M_v + u) * M_v;
   for (int j = lane; j < M_v; j += 64) keys[j] = order_key(row[j]);
   __syncthreads();
@@ -170,7 +175,8 @@ size_t ws_select_mask(const dfs_geom* g, const dfs_sizes& s) {
 int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, int mode, double sparsity, double mass,
                     uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max, int32_t* k_head, void* ws,
                     hipStream_t st) {
-  if (mode != DFS_SELECT_TOPK && mode != DFS_SELECT_MASS_HEAD) return fail(DFS_EINVAL, "dfs_select_mask: unknown mode %d", mode);
+  if (mode != DFS_SELECT_TOPK && mode != DFS_SELECT_MASS_HEAD && mode != DFS_SELECT_MASS_ROW)
+    return fail(DFS_EINVAL, "dfs_select_mask: unknown mode %d", mode);
   if (!(sparsity >= 0.0 && sparsity <= 1.0)) return fail(DFS_EINVAL, "dfs_select_mask: sparsity %g is outside [0,1]", sparsity);
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
   if (s.M_v > 16384) return fail(DFS_ESHAPE, "dfs_select_mask: M_v=%d exceeds 16384 (one score row must fit in 64 KB of LDS)", s.M_v);
@@ -180,7 +186,7 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
   const size_t lds = size_t(s.M_v) * sizeof(uint32_t);
   dim3 rows(unsigned(s.M), unsigned(g->heads));
   if (mode == DFS_SELECT_TOPK) {
-    select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, k_base, nullptr, mask, kv_idx, kv_cnt, K_max, k_head);
+    select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, k_base, nullptr, nullptr, 0, mask, kv_idx, kv_cnt, K_max, k_head);
   } else {
     if (!(mass > 0.0 && mass <= 1.0)) return fail(DFS_EINVAL, "dfs_select_mask: mass %g is outside (0,1]", mass);
     int32_t* k_row = static_cast<int32_t*>(ws);
@@ -188,8 +194,12 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
     int k_cap = K_max - s.M_x;
     if (k_cap > s.M_v) k_cap = s.M_v;
     mass_count_kernel<<<dim3(unsigned(s.M_v), unsigned(g->heads)), 64, lds, st>>>(score, s.M_v, mass, k_row);
-    head_count_kernel<<<dim3(unsigned(g->heads)), 256, 0, st>>>(k_row, s.M_v, k_base, k_cap, k_used, k_head);
-    select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, 0, k_used, mask, kv_idx, kv_cnt, K_max, nullptr);
+    if (mode == DFS_SELECT_MASS_HEAD) {
+      head_count_kernel<<<dim3(unsigned(g->heads)), 256, 0, st>>>(k_row, s.M_v, k_base, k_cap, k_used, k_head);
+      select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, 0, k_used, nullptr, 0, mask, kv_idx, kv_cnt, K_max, nullptr);
+    } else {
+      select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, k_base, nullptr, k_row, k_cap, mask, kv_idx, kv_cnt, K_max, nullptr);
+    }
   }
   return launch_status("dfs_select_mask");
 }
@@ -206,7 +216,7 @@ extern "C" int dfs_select_mask(const dfs_geom* g, const float* score, int mode, 
   if (rc) return rc;
   if (!score || !kv_idx || !kv_cnt) return fail(DFS_EINVAL, "dfs_select_mask: NULL argument");
   const size_t need = ws_select_mask(g, s);
-  if (mode == DFS_SELECT_MASS_HEAD && (!ws || (uintptr_t(ws) & 255) || ws_bytes < need))
+  if ((mode == DFS_SELECT_MASS_HEAD || mode == DFS_SELECT_MASS_ROW) && (!ws || (uintptr_t(ws) & 255) || ws_bytes < need))
     return fail(DFS_EWORKSPACE, "dfs_select_mask: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
   return run_select_mask(g, s, score, mode, sparsity, mass, mask, kv_idx, kv_cnt, K_max, k_head, ws, as_stream(stream));
 }

@@ -130,6 +130,11 @@ def test_score_and_select_small(w):
     mask_o, k_head_o = O.select_mass_head(score_np, 0.8, 0.9, sz["M_x"])
     assert np.array_equal(st.k_head.cpu().numpy(), k_head_o)
     assert np.array_equal(st.mask.cpu().numpy(), mask_o)
+    # adaptive per-row ratio: every row its own count; the attention kernel runs on lists of unequal length
+    st = G.gpu_select(g, score, P.DFS_SELECT_MASS_ROW, 0.9, mass=0.8)
+    mask_o, k_row_o = O.select_mass_row(score_np, 0.8, 0.9, sz["M_x"])
+    assert np.array_equal(st.mask.cpu().numpy(), mask_o)
+    assert np.array_equal(st.kv_cnt.cpu().numpy()[:, :sz["M_v"]], k_row_o + sz["M_x"])
 
 
 def test_select_ties_and_edge_rows():
@@ -206,6 +211,8 @@ def test_attention_small_full(w):
     for sp in (w.sparsity[0], 0.0):
         st = G.gpu_select(g, score, P.DFS_SELECT_TOPK, sp)
         _compare_attention(w, g, dt, qp, kp, vp, st, st.mask.cpu().numpy(), blk_valid, range(sz["M"]))
+    st = G.gpu_select(g, score, P.DFS_SELECT_MASS_ROW, 0.9, mass=0.7)     # lists of unequal length
+    _compare_attention(w, g, dt, qp, kp, vp, st, st.mask.cpu().numpy(), blk_valid, range(sz["M"]))
     # an arbitrary mask with an empty row and a single-block row, through host-built lists
     rng = np.random.default_rng(5)
     mask = (rng.random((w.heads, sz["M"], sz["M"])) < 0.4).astype(np.uint8)

@@ -201,3 +201,24 @@ def test_mass_rule_brute_force_mean():
         assert abs(int(k_head[h]) - want) <= 1      # fixed point vs float may move one row's k by one
         for u in range(M_v):
             assert list(np.nonzero(mask[h, u])[0]) == _brute_topk_row(score[h, u], int(k_head[h]))
+
+
+def test_mass_row_rule():
+    M_v = 40
+    score = np.zeros((1, M_v, M_v), dtype=np.float32)
+    score[0, :, :] = 1e-3
+    score[0, 0, 7] = 10.0                                   # one dominant block: k = floor
+    score[0, 1, :] = 0.1                                    # uniform: k = ceil(mass * M_v)
+    geo = (0.5 ** np.arange(1, M_v + 1)).astype(np.float32)
+    score[0, 2, :] = geo[::-1]                              # geometric: k = 4 for mass 0.9
+    mask, k_row = O.select_mass_row(score, 0.9, 0.95)
+    assert list(k_row[0, :3]) == [2, 36, 4]
+    assert list(np.nonzero(mask[0, 0])[0]) == [0, 7]        # the dominant block, then the lowest-index tie
+    assert list(np.nonzero(mask[0, 2])[0]) == [36, 37, 38, 39]
+    assert np.array_equal(mask[0].sum(axis=1), k_row[0])
+    # against the per-head rule: the head count is the rounded-up mean of the per-row counts (floor applied after)
+    rng = np.random.default_rng(9)
+    sc = (rng.random((2, M_v, M_v)) ** 5).astype(np.float32)
+    _, k_row = O.select_mass_row(sc, 0.8, 1.0 - 1.0 / M_v)  # cap so loose that the floor is one block
+    _, k_head = O.select_mass_head(sc, 0.8, 1.0 - 1.0 / M_v)
+    assert list(k_head) == [math.ceil(k_row[h].sum() / M_v) for h in range(2)]
