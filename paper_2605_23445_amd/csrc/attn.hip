@@ -66,7 +66,9 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   constexpr int STEPS = BM / KN;                   // tiles per key block
   constexpr int NF = D / 8;                        // operand fragments per stage: D/16 of V^T, D/16 of K
   constexpr int SLOTS = NF * QT;                   // matrix instructions per stage
-  constexpr int SLICES = 13 * QT;                  // softmax slices per stage
+  constexpr int ESL = 12;                          // slices the sixteen exponentials of a query tile are spread over
+  constexpr int SL = 5 + ESL;                      // softmax slices per query tile: 4 for the maximum, ESL, 1 to close
+  constexpr int SLICES = SL * QT;                  // softmax slices per stage
   constexpr int STAGE_LEN = SLOTS > SLICES ? SLOTS : SLICES;
   constexpr float TAU = 8.f;                       // rescale only when the row maximum grows by > 2^TAU
   // Two K and two V tile buffers (tile t lives in the pair of parity t & 1).
@@ -278,7 +280,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         }
       }
       if (m < SLICES) {
-        const int a = m / 13, ph = m % 13;
+        const int a = m / SL, ph = m % SL;
         const f32x16& x = sx[a];
         if (ph == 0) {
           mx_a = fmaxf(fmaxf(x[0], x[1]), x[2]);
@@ -302,14 +304,23 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
           m_use = m_new == -INFINITY ? 0.f : m_new;   // a row that has seen only pad keys
           mc = m_use * c2;
           asm volatile("" : "+v"(mc));
-        } else if (ph < 12) {                         // eight slices of two probabilities each
-          const int i = 2 * (ph - 4);
-          pe[i] = __builtin_amdgcn_exp2f(fmaf(x[i], c2, -mc));
-          pe[i + 1] = __builtin_amdgcn_exp2f(fmaf(x[i + 1], c2, -mc));
-          asm volatile("" : "+v"(pe[i]), "+v"(pe[i + 1]));
-          if (i > 0) pack(a, i - 2);                  // one slice behind, so the exponentials have retired
+        } else if (ph < 4 + ESL) {                    // the sixteen probabilities, spread evenly over ESL slices
+          const int eb = (ph - 4) * 16 / ESL, ee = (ph - 3) * 16 / ESL;
+#pragma unroll
+          for (int i = eb; i < ee; ++i) {
+            pe[i] = __builtin_amdgcn_exp2f(fmaf(x[i], c2, -mc));
+            asm volatile("" : "+v"(pe[i]));
+          }
+          if (ph > 4) {                               // pairs completed by the previous slice: its exponentials have retired
+            const int pb = (ph - 5) * 16 / ESL, pe_ = (ph - 4) * 16 / ESL;
+#pragma unroll
+            for (int i = pb; i < pe_; ++i)
+              if (i % 2 == 1) pack(a, i - 1);
+          }
         } else {
-          pack(a, 14);
+#pragma unroll
+          for (int i = (ESL - 1) * 16 / ESL; i < 16; ++i)
+            if (i % 2 == 1) pack(a, i - 1);
           alpha[a] = __builtin_amdgcn_exp2f((m_run[a] - m_use) * c2);   // 1 unless the maximum moved
           moved[a] = __builtin_amdgcn_ballot_w64(move) != 0;
           m_run[a] = m_new;
