@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_e
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int32_t* __restrict__ kv_idx, const int32_t* __restrict__ kv_cnt, int K_max, uint16_t* __restrict__ o,
                  float* __restrict__ lse, const int32_t* __restrict__ row_index, int64_t N_src, int64_t N_pad, int64_t N_v, int n_text,
-                 int M_v, int M, int total_wg, int wg_per_xcd, int head_major, float scale) {
+                 int M_v, int M, int total_wg, int wg_per_xcd, int mapping, float scale) {
   constexpr int NW = BM / (32 * QT);               // waves: one per 32 QT query rows
   constexpr int CH = D / 8;                        // 16-byte chunks per row
   constexpr int TILE = KN * D;                     // elements per tile
@@ -77,15 +77,38 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   __shared__ __attribute__((aligned(16))) uint16_t sV0[TILE];
   __shared__ __attribute__((aligned(16))) uint16_t sV1[TILE];
 
-  // Work-group to (head, query block).  Ids are dealt round-robin to the 8 XCDs.  head_major: each XCD
-  // walks the query blocks of its own heads (neighbouring blocks, which share key blocks, meet in one
-  // L2).  Otherwise all XCDs work on the same head at a time, so the key/value working set of the
-  // chip is one or two heads and stays in the memory-side cache.  Query blocks are taken last-first:
-  // the dense text blocks at the end of a head start first.
-  const int logical = head_major ? (blockIdx.x % 8) * wg_per_xcd + blockIdx.x / 8 : blockIdx.x;
-  if (logical >= total_wg) return;
-  const int head = logical / M;
-  const int u = M - 1 - logical % M;
+  // Work-group to (head, query block).  Ids are dealt round-robin to the 8 XCDs, so id % 8 names the XCD
+  // and id / 8 the order inside it.
+  //   mapping 2 (long sequences): every XCD takes its own eighth of the query blocks of head 0, then of
+  //     head 1, ...  All XCDs are on the same head at the same time, so the key/value working set of the
+  //     chip is one or two heads and stays in the memory-side cache, while the blocks that meet in one
+  //     L2 are neighbours on the curve, which share key blocks.  The dense text blocks of all heads, the
+  //     longest work-groups, come first.
+  //   mapping 1 (an eighth of a head would not fill an XCD): each XCD walks whole heads of its own,
+  //     query blocks last-first so that the text blocks of a head start first.
+  //   mapping 0: ids in plain order.
+  int head, u;
+  if (mapping == 2) {
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int M_x = M - M_v, n_heads = total_wg / M;
+    const int text_slots = (n_heads * M_x + 7) / 8;
+    if (slot < text_slots) {
+      const int id = slot * 8 + xcd;
+      if (id >= n_heads * M_x) return;
+      head = id / M_x;
+      u = M_v + id % M_x;
+    } else {
+      const int C = (M_v + 7) / 8, s2 = slot - text_slots;
+      head = s2 / C;
+      u = xcd * C + s2 % C;
+      if (head >= n_heads || u >= M_v) return;
+    }
+  } else {
+    const int logical = mapping ? (blockIdx.x % 8) * wg_per_xcd + blockIdx.x / 8 : blockIdx.x;
+    if (logical >= total_wg) return;
+    head = logical / M;
+    u = M - 1 - logical % M;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
@@ -521,14 +544,17 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   if (dtype == DFS_BF16) {
     const int64_t total = int64_t(g->heads) * s.M;
     if (total > (int64_t(1) << 30)) return fail(DFS_ESHAPE, "dfs_sparse_attn_fwd: heads*M too large");
-    const int per_xcd = int((total + 7) / 8);
+    // an eighth of a head's video blocks per XCD once that fills the XCD's 64 work-group slots (measured
+    // +3..6 % on the 75 600- and 118 800-token shapes, -4 % on the 17 550-token one, which stays on mapping 1)
+    const int chunk = (s.M_v + 7) / 8;
+    const int mapping = chunk >= 64 ? 2 : 1;
+    const int per_xcd = mapping == 2 ? (g->heads * s.M_x + 7) / 8 + g->heads * chunk : int((total + 7) / 8);
     dim3 grid(unsigned(per_xcd * 8));
-    const int head_major = 1;                        // measured equal to the interleaved mapping on the benchmark shapes
 #define ATTN(DD, BB, QQ)                                                                                                    \
   attn_bf16_kernel<DD, BB, QQ><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
                                                              static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
                                                              static_cast<uint16_t*>(o), lse, row_index, s.N, s.N_pad, s.N_v,  \
-                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, head_major, scale)
+                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, mapping, scale)
     if (g->d == 64) { if (g->B == 64) ATTN(64, 64, 1); else ATTN(64, 128, 1); }
     else            { if (g->B == 64) ATTN(128, 64, 1); else ATTN(128, 128, 1); }
 #undef ATTN

@@ -370,6 +370,71 @@ def test_full_size_workloads(name, oracle_heads):
         _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, blocks, heads_idx=list(oracle_heads))
 
 
+def test_full_size_caching_schedule():
+    """The mask-caching workload at full size (75 600 tokens, 40 heads), first steps of its schedule through
+    the one-call entry point: refresh at steps 0 and 5 with the adaptive per-head ratio, reuse in between
+    while Q and K drift.  At each refresh the per-head keep counts and the masks of all heads equal the
+    oracle's selection on the GPU's scores; reuse steps leave the mask untouched; outputs are compared on
+    sampled query blocks of two heads at a refresh step and at the reuse step with the largest drift."""
+    w = CONFIGS["wan_cache"]
+    sz = derived_sizes(w)
+    say(f"full size {w.name}: heads {w.heads} N {sz['N']} delta {w.delta} mass {w.mass} cap {w.cap}")
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, blk_valid_d = G.gpu_perm(g)
+    blk_valid = blk_valid_d.cpu().numpy()
+    qf = torch.from_numpy(bf16_bits_to_f32(q)).cuda(); kf = torch.from_numpy(bf16_bits_to_f32(k)).cuda()
+    vd = G.to_dev(v)
+    del q, k, v
+    gen = torch.Generator(device="cuda"); gen.manual_seed(w.seed)
+    K_max = sz["M"]
+    st = P.MaskState(torch.zeros((w.heads, sz["M"], K_max), dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"]), dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"], sz["M"]), dtype=torch.uint8, device="cuda"),
+                     torch.zeros((w.heads,), dtype=torch.int32, device="cuda"), K_max)
+    ws = G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_FORWARD_BF16))
+    o = torch.empty_like(vd)
+    heads_idx = [3, 36]
+    blocks = _sample_blocks(sz["M_v"], sz["M"], w.seed, n=4)
+    g1 = P.Geom(w.T, w.H, w.W, w.n_text, 1, w.d, w.B, w.Bs)
+    perm_np = perm_pad.cpu().numpy()
+    mask_prev = None
+    for t in range(7):
+        if t:
+            qf += w.drift * torch.randn(qf.shape, generator=gen, device="cuda")
+            kf += w.drift * torch.randn(kf.shape, generator=gen, device="cuda")
+        qd, kd = qf.to(torch.bfloat16), kf.to(torch.bfloat16)
+        refresh = t % w.delta == 0
+        P.dfs_forward(g, dt, qd, kd, vd, perm_pad, inv, refresh, P.DFS_SELECT_MASS_HEAD, w.cap, w.mass, st, 1 / math.sqrt(w.d), o, ws)
+        mask = st.mask.cpu().numpy()
+        if refresh:
+            qp, kp = (G.gpu_permute(g, dt, x, perm_pad) for x in (qd, kd))
+            score = G.gpu_score(g, dt, qp, kp).cpu().numpy()
+            del qp, kp
+            mask_o, k_head_o = O.select_mass_head(score, w.mass, w.cap)
+            k_head = st.k_head.cpu().numpy()
+            say(f"  step {t}: refresh, kept blocks per row: min {k_head.min()} mean {k_head.mean():.1f} max {k_head.max()}")
+            assert np.array_equal(k_head, k_head_o) and np.array_equal(mask, mask_o)
+        else:
+            assert np.array_equal(mask, mask_prev)
+        mask_prev = mask
+        if t in (0, 4, 5):
+            got = G.as_f64_dev(o[heads_idx])
+            worst, total, count = 0.0, 0.0, 0
+            for i, h in enumerate(heads_idx):
+                qh, kh, vh = (G.as_f64_dev(G.gpu_permute(g1, dt, x[h:h + 1].contiguous(), perm_pad)[0])
+                              for x in (qd, kd, vd))
+                for u in blocks:
+                    cols = np.nonzero(mask[h, u])[0]
+                    want, _ = O.sparse_attn_block(qh, kh, vh, cols, blk_valid, w.B, u, 1.0 / math.sqrt(w.d))
+                    pos = np.arange(u * w.B, u * w.B + blk_valid[u])
+                    src = perm_np[pos]
+                    err = np.abs(got[i][src] - want[:blk_valid[u]])
+                    worst = max(worst, err.max()); total += err.sum(); count += err.size
+            say(f"  step {t}: output max err {worst:.3e} mean err {total / count:.3e} over {count} values")
+            assert worst <= BF16_MAX and total / count <= BF16_MEAN
+
+
 @pytest.mark.parametrize("w", [MID_BF16, MID_D64, MID_B64], ids=lambda w: w.name)
 def test_source_order_variants_are_bit_identical(w):
     """dfs_block_score_src / dfs_sparse_attn_fwd_src (Q gathered, O scattered through the permutation) give the
