@@ -146,6 +146,19 @@ def main():
     stage_ms = {name: sum(events[s * 7 + i].elapsed_time(events[s * 7 + i + 1]) for s in range(a.steps)) / a.steps
                 for i, name in enumerate(stages)}
 
+    # Shader clock under the attention kernel, from two extra untimed steps with the kernel's own clock probe
+    # (cycle counter against the constant-rate 100 MHz counter): the chip runs well below its nominal 2.4 GHz
+    # under matrix load, so the nominal-peak fraction understates how busy the matrix cores are per cycle.
+    clock_mhz = None
+    if fused:
+        probe = torch.zeros(3, dtype=torch.int64, device="cuda")
+        P.dfs_attn_clock_probe(probe)
+        step(); step()
+        torch.cuda.synchronize()
+        P.dfs_attn_clock_probe(None)
+        pc = probe.cpu().numpy().astype(np.float64)
+        clock_mhz = float(pc[0] / pc[1] * 100.0) if pc[1] > 0 else None
+
     cnt = kv_cnt.cpu().numpy().astype(np.int64)
     pairs = int(cnt.sum())
     flop_exec = pairs * 4.0 * w.B * w.B * w.d
@@ -177,6 +190,9 @@ def main():
         "attn_executed_tflops": flop_exec / (attn_ms * 1e-3) / 1e12,
         "attn_dense_equiv_tflops": flop_dense / (attn_ms * 1e-3) / 1e12,
         "mfma_util_pct": 100.0 * flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "attn_shader_clock_mhz": clock_mhz,
+        "mfma_util_pct_at_measured_clock": None if not clock_mhz else
+            100.0 * flop_exec / (attn_ms * 1e-3) / (256 * 4 * 1024.0 * clock_mhz * 1e6),
         "stage_ms": {k2: round(v2, 4) for k2, v2 in stage_ms.items()},
         "permute_gbs": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9,
         "unperm_gbs": None if fused else bytes_unperm / (stage_ms["unperm"] * 1e-3) / 1e9,

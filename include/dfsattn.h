@@ -245,6 +245,16 @@ int dfs_recall(const dfs_geom* g, const float* lse_sparse, const float* lse_dens
 int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_keep, int32_t* dense, int32_t* refresh,
                  double* sparsity);
 
+/*
+ * Diagnostic for measurements, not part of the method: while `counters` (device memory, 3 x uint64, zeroed by
+ * the caller) is set, every work-group of the bf16 attention kernel adds to counters[0] the shader-clock
+ * cycles and to counters[1] the constant-rate timer ticks (100 MHz) between its start and its end, and 1 to
+ * counters[2].  counters[0] / counters[1] x 100 MHz is the shader clock the kernel ran at, which on this chip
+ * sits well below the nominal 2.4 GHz under matrix load.  NULL switches it off (the default).  Process-wide
+ * state, not thread-safe; the buffer must stay valid while set.
+ */
+int dfs_attn_clock_probe(uint64_t* counters);
+
 #ifdef __cplusplus
 }
 #endif

@@ -74,6 +74,7 @@ def _load():
         "dfs_unperm": (C.c_int, [gp, C.c_int, vp, vp, vp, vp]),
         "dfs_block_score_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, sz, vp]),
         "dfs_sparse_attn_fwd_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]),
+        "dfs_attn_clock_probe": (C.c_int, [vp]),
         "dfs_forward": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, dbl, dbl,
                                   C.POINTER(_MaskStateC), f32, vp, vp, sz, vp]),
     }
@@ -86,7 +87,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
            "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
-           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src")
+           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe")
 DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
 
@@ -232,6 +233,12 @@ def dfs_sparse_attn_fwd_src(g: Geom, dtype: int, q, perm_pad, k_perm, v_perm, kv
                                         _ptr(kv_idx, torch.int32, g.heads * s.M * K_max, "kv_idx"),
                                         _ptr(kv_cnt, torch.int32, g.heads * s.M, "kv_cnt"), int(K_max), float(scale),
                                         _ptr(o, td, n_src, "o"), _ptr(lse, torch.float32, g.heads * s.N_pad, "lse"), _stream()))
+
+
+def dfs_attn_clock_probe(counters: torch.Tensor | None):
+    """Diagnostic: accumulate shader-clock cycles / 100 MHz ticks / work-group count of the bf16 attention
+    kernel into `counters` (3 x int64 on the device, zeroed by the caller); None switches it off."""
+    _check(_lib.dfs_attn_clock_probe(_ptr(counters, torch.int64, 3, "counters")))
 
 
 def dfs_unperm(g: Geom, dtype: int, o_perm, inv, o):

@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_e
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int32_t* __restrict__ kv_idx, const int32_t* __restrict__ kv_cnt, int K_max, uint16_t* __restrict__ o,
                  float* __restrict__ lse, const int32_t* __restrict__ row_index, int64_t N_src, int64_t N_pad, int64_t N_v, int n_text,
-                 int M_v, int M, int total_wg, int wg_per_xcd, int mapping, float scale) {
+                 int M_v, int M, int total_wg, int wg_per_xcd, int mapping, float scale, unsigned long long* __restrict__ clock_probe) {
   constexpr int NW = BM / (32 * QT);               // waves: one per 32 QT query rows
   constexpr int CH = D / 8;                        // 16-byte chunks per row
   constexpr int TILE = KN * D;                     // elements per tile
@@ -109,6 +109,9 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     head = logical / M;
     u = M - 1 - logical % M;
   }
+
+  // diagnostic: shader-clock cycles and constant-rate (100 MHz) ticks this work-group lives for
+  const unsigned long long probe_c0 = clock_probe ? clock64() : 0, probe_w0 = clock_probe ? wall_clock64() : 0;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
@@ -433,6 +436,11 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
   }
 
+  if (clock_probe && tid == 0) {
+    atomicAdd(&clock_probe[0], clock64() - probe_c0);
+    atomicAdd(&clock_probe[1], wall_clock64() - probe_w0);
+    atomicAdd(&clock_probe[2], 1ull);
+  }
   // epilogue: normalise, round to bf16, store.  Lane (n, h) holds O[row][32 dt + 8 j + 4 h + 0..3].
 #pragma unroll
   for (int a = 0; a < QT; ++a) {
@@ -537,6 +545,8 @@ __global__ void __launch_bounds__(128) attn_f32_kernel(const float* __restrict__
   if (lse) lse[int64_t(head) * N_pad + q_row] = l_run > 0.f ? m_run + __logf(l_run) : -INFINITY;
 }
 
+static unsigned long long* g_clock_probe = nullptr;   // set by dfs_attn_clock_probe (diagnostic)
+
 int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q, const void* k, const void* v,
                     const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale, void* o, float* lse,
                     const int32_t* row_index, hipStream_t st) {
@@ -554,7 +564,7 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   attn_bf16_kernel<DD, BB, QQ><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
                                                              static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
                                                              static_cast<uint16_t*>(o), lse, row_index, s.N, s.N_pad, s.N_v,  \
-                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, mapping, scale)
+                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, mapping, scale, g_clock_probe)
     if (g->d == 64) { if (g->B == 64) ATTN(64, 64, 1); else ATTN(64, 128, 1); }
     else            { if (g->B == 64) ATTN(128, 64, 1); else ATTN(128, 128, 1); }
 #undef ATTN
@@ -577,6 +587,11 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
 }  // namespace dfs
 
 using namespace dfs;
+
+extern "C" int dfs_attn_clock_probe(uint64_t* counters) {
+  g_clock_probe = reinterpret_cast<unsigned long long*>(counters);
+  return DFS_OK;
+}
 
 extern "C" int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm, const void* v_perm,
                                    const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale, void* o_perm,

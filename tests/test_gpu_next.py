@@ -109,3 +109,30 @@ def test_paper_schedule_run():
     assert [d for d, _, _ in log] == [True, True, False, False, False, False, False, False]
     assert [s for _, _, s in log[2:]] == [0.7, 0.7, 0.8, 0.8, 0.9, 0.9]
     assert [r for _, r, _ in log[2:]] == [True, True, True, False, True, False]
+
+
+def test_attention_clock_probe_counts_every_work_group():
+    """The measurement diagnostic: with the probe set, every (head, query block) work-group of the bf16
+    attention kernel reports once, the output is unchanged, and the clock ratio is a plausible shader clock."""
+    w = Workload("probe", 5, 12, 20, heads=3, d=128, dtype="bf16", B=128, Bs=32, sparsity=(0.6,), seed=5)
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    qp, kp, vp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k, v))
+    st = G.gpu_select(g, G.gpu_score(g, dt, qp, kp), P.DFS_SELECT_TOPK, 0.6)
+    o_ref, _ = G.gpu_attn(g, dt, qp, kp, vp, st)
+    probe = torch.zeros(3, dtype=torch.int64, device="cuda")
+    P.dfs_attn_clock_probe(probe)
+    try:
+        o_probe, _ = G.gpu_attn(g, dt, qp, kp, vp, st)
+        torch.cuda.synchronize()
+    finally:
+        P.dfs_attn_clock_probe(None)
+    cycles, ticks, groups = (int(x) for x in probe.cpu())
+    assert groups == w.heads * sz["M"]
+    assert torch.equal(o_ref.view(torch.int16), o_probe.view(torch.int16))
+    assert ticks > 0 and 300.0 < cycles / ticks * 100.0 < 3000.0
+    o_again, _ = G.gpu_attn(g, dt, qp, kp, vp, st)
+    torch.cuda.synchronize()
+    assert int(probe.cpu()[2]) == groups          # switched off again
