@@ -52,6 +52,21 @@ constexpr int swz_period(int step, int mod) {    // smallest P with (P * step) %
 // file, i.e. one wave per SIMD, and a lone wave overlaps its matrix, vector and LDS work worse than two
 // waves do: measured slower (about 880 against 1030 TFLOP/s on cache-resident keys), so QT = 1 is
 // what is launched.
+// Maxima as single instructions.  (fmaxf on raw matrix-instruction results makes the compiler add a
+// canonicalising v_max per input.)  The inputs are logits or -inf, never NaN.  The instructions read
+// results of matrix instructions issued at least a whole softmax slice plus a stage prologue earlier,
+// far beyond the wait states such a read needs.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float max2(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 template <int D, int BM, int QT>
 __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_eu(2 / QT, 2 / QT)))
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -153,8 +168,12 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
       for (int i = 0; i < 16; ++i) oacc[a][dt][i] = 0.f;
   float m_run[QT], l_run[QT];
+  // m_run is the reference maximum in the base-2 exponent's units (logit x c2).  It starts at a large
+  // finite negative value instead of -inf, so that a row that has only met pad keys (all logits -inf)
+  // needs no special case: its differences stay finite and its probabilities are exp2(-inf) = 0.
+  constexpr float M_START = -1.0e30f;
 #pragma unroll
-  for (int a = 0; a < QT; ++a) { m_run[a] = -INFINITY; l_run[a] = 0.f; }
+  for (int a = 0; a < QT; ++a) { m_run[a] = M_START; l_run[a] = 0.f; }
   const float c2 = scale * 1.4426950408889634f;     // softmax in base 2
 
   // Tile loads, global memory straight into LDS: instruction j of this wave fills the 64 consecutive
@@ -257,8 +276,8 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   // accumulators are rescaled rarely; probabilities stay below 2^TAU, which is exact in the final
   // ratio.  Scheduling fences and empty asm statements keep the compiler from separating the matrix and
   // vector work again.  alpha[a] is the factor accumulator a must be multiplied by after the stage.
-  auto stage = [&](auto do_pv, auto do_s, const uint16_t* vbuf, int pv_half, const bf16x8 (&pp)[QT][2], const uint16_t* kbuf,
-                   int s_half, f32x16 (&sn)[QT], const f32x16 (&sx)[QT], bf16x8 (&pc)[QT][2], float (&alpha)[QT], bool (&moved)[QT]) {
+  auto stage = [&](auto do_pv, auto do_s, const uint16_t* vbuf, int pv_half, const u32x4 (&pp)[QT][2], const uint16_t* kbuf,
+                   int s_half, f32x16 (&sn)[QT], const f32x16 (&sx)[QT], u32x4 (&pc)[QT][2], float (&alpha)[QT], bool (&moved)[QT]) {
     constexpr bool DO_PV = decltype(do_pv)::value, DO_S = decltype(do_s)::value;
     const uint16_t* tV = vbuf + (32 * pv_half + v_row) * D + v_b;
     const uint16_t* tK = kbuf + (32 * s_half + n) * D;
@@ -270,16 +289,16 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         frag[f] = k_frag(tK, f / 2);
       }
     };
-    float mx_a = 0.f, mx_b = 0.f, mx_c = 0.f, mx_d = 0.f, mx = 0.f, m_new = 0.f, m_use = 0.f, mc = 0.f, psum = 0.f;
+    float mx_a = 0.f, mx_b = 0.f, mx_c = 0.f, mx_d = 0.f, mx = 0.f, mc = 0.f, psum = 0.f;
     bool move = false;
     float pe[16];
     // Rounds a pair of probabilities to bf16 and adds them, as rounded, to the normaliser: numerator and
     // denominator then use exactly the same weights, so a dominant key leaves no systematic rounding bias.
+    // The pair is one 32-bit register of the next product's B operand.
     auto pack = [&](int a, int i) {
       const bf16x2 pk = {(__bf16)pe[i], (__bf16)pe[i + 1]};
       psum = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, psum, false);
-      pc[a][i / 8][i % 8] = pk[0];
-      pc[a][i / 8][i % 8 + 1] = pk[1];
+      pc[a][i / 8][(i % 8) / 2] = __builtin_bit_cast(uint32_t, pk);
     };
     if (DO_S) {
 #pragma unroll
@@ -299,7 +318,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         if (f % 2 == 0) {
           if (DO_PV) {
             const int j = f / 2, s2 = j / (D / 32), dt = j % (D / 32);
-            oacc[a][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f], pp[a][s2], oacc[a][dt], 0, 0, 0);
+            oacc[a][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f], __builtin_bit_cast(bf16x8, pp[a][s2]), oacc[a][dt], 0, 0, 0);
           }
         } else if (DO_S) {
           sn[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[f], qf[a][f / 2], sn[a], 0, 0, 0);
@@ -309,26 +328,24 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         const int a = m / SL, ph = m % SL;
         const f32x16& x = sx[a];
         if (ph == 0) {
-          mx_a = fmaxf(fmaxf(x[0], x[1]), x[2]);
-          mx_b = fmaxf(fmaxf(x[3], x[4]), x[5]);
-          mx_c = fmaxf(fmaxf(x[6], x[7]), x[8]);
-          mx_d = fmaxf(fmaxf(x[9], x[10]), x[11]);
+          mx_a = max3(x[0], x[1], x[2]);
+          mx_b = max3(x[3], x[4], x[5]);
+          mx_c = max3(x[6], x[7], x[8]);
+          mx_d = max3(x[9], x[10], x[11]);
           psum = 0.f;
         } else if (ph == 1) {
-          mx_a = fmaxf(fmaxf(mx_a, mx_b), mx_c);
-          mx_d = fmaxf(fmaxf(mx_d, x[12]), x[13]);
-          mx_a = fmaxf(fmaxf(mx_a, x[14]), x[15]);
-          mx = fmaxf(mx_a, mx_d);
+          mx_a = max3(mx_a, mx_b, mx_c);
+          mx_d = max3(mx_d, x[12], x[13]);
+          mx_a = max3(mx_a, x[14], x[15]);
+          mx = max2(mx_a, mx_d);
           asm volatile("" : "+v"(mx));                 // keeps the slice in its slot (its result is needed only later)
         } else if (ph == 2) {
           const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-          mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          mx = max2(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * c2;
           asm volatile("" : "+v"(mx));
         } else if (ph == 3) {
-          move = (mx - m_run[a]) * c2 > TAU;          // true on the first real half tile (m_run = -inf)
-          m_new = move ? mx : m_run[a];
-          m_use = m_new == -INFINITY ? 0.f : m_new;   // a row that has seen only pad keys
-          mc = m_use * c2;
+          move = mx - m_run[a] > TAU;                  // true on the first real half tile (m_run = M_START)
+          mc = move ? mx : m_run[a];
           asm volatile("" : "+v"(mc));
         } else if (ph < 4 + ESL) {                    // the sixteen probabilities, spread evenly over ESL slices
           const int eb = (ph - 4) * 16 / ESL, ee = (ph - 3) * 16 / ESL;
@@ -347,9 +364,9 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
           for (int i = (ESL - 1) * 16 / ESL; i < 16; ++i)
             if (i % 2 == 1) pack(a, i - 1);
-          alpha[a] = __builtin_amdgcn_exp2f((m_run[a] - m_use) * c2);   // 1 unless the maximum moved
+          alpha[a] = __builtin_amdgcn_exp2f(m_run[a] - mc);              // 1 unless the maximum moved
           moved[a] = __builtin_amdgcn_ballot_w64(move) != 0;
-          m_run[a] = m_new;
+          m_run[a] = mc;
           l_run[a] = l_run[a] * alpha[a] + psum;
           asm volatile("" : "+v"(l_run[a]), "+v"(alpha[a]));
         }
@@ -380,7 +397,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   // barrier in the middle of tile t, into the buffers K(t) and V(t-1) have just left; they are first
   // read a full tile later.
   f32x16 s0[QT], s1[QT];
-  bf16x8 p0[QT][2], p1[QT][2];
+  u32x4 p0[QT][2], p1[QT][2];                      // probabilities as bf16 pairs: B operands of the products
   auto tile_step = [&](auto parity, auto first, auto last, int t) {
     constexpr bool ODD = decltype(parity)::value, FIRST = decltype(first)::value, LAST = decltype(last)::value;
     uint16_t* k_cur = ODD ? sK1 : sK0;             // K(t); K(t+2) goes here
@@ -432,7 +449,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
       const bf16x8 f = v_frag(tV, j);
 #pragma unroll
       for (int a = 0; a < QT; ++a)
-        oacc[a][j % (D / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, p1[a][j / (D / 32)], oacc[a][j % (D / 32)], 0, 0, 0);
+        oacc[a][j % (D / 32)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, __builtin_bit_cast(bf16x8, p1[a][j / (D / 32)]), oacc[a][j % (D / 32)], 0, 0, 0);
     }
   }
 
@@ -460,7 +477,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
     if (lse && h == 0)
       lse[int64_t(head) * N_pad + q_row0 + 32 * a] =
-          l_tot > 0.f ? (m_run[a] * c2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+          l_tot > 0.f ? (m_run[a] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   }
 }
 
