@@ -46,12 +46,6 @@ constexpr int swz_period(int step, int mod) {    // smallest P with (P * step) %
   return p;
 }
 
-// QT = 32-row query tiles per wave.  With QT = 2 every K / V^T fragment read from LDS feeds two
-// matrix instructions, which halves the LDS bytes per matrix instruction (1 KB at QT = 1, and LDS
-// supplies 128 B per clock per CU), but at d = 128 the accumulators then need the whole register
-// file, i.e. one wave per SIMD, and a lone wave overlaps its matrix, vector and LDS work worse than two
-// waves do: measured slower (about 880 against 1030 TFLOP/s on cache-resident keys), so QT = 1 is
-// what is launched.
 // Maxima as single instructions.  (fmaxf on raw matrix-instruction results makes the compiler add a
 // canonicalising v_max per input.)  The inputs are logits or -inf, never NaN.  The instructions read
 // results of matrix instructions issued at least a whole softmax slice plus a stage prologue earlier,
@@ -67,6 +61,13 @@ __device__ __forceinline__ float max2(float a, float b) {
   return r;
 }
 
+// QT = 32-row query tiles per wave.  With QT = 2 every K / V^T fragment read from LDS feeds two
+// matrix instructions, which halves the LDS bytes per matrix instruction, but at d = 128 the
+// accumulators then need the whole register file, i.e. one wave per SIMD.  Measured: the lone wave runs
+// at a higher clock (2.1 against 1.8 GHz, it draws less power) but keeps the matrix cores busy only
+// 43 % of the cycles against 57 % for two waves: a wave issues in order, about one instruction per five
+// cycles, and one wave's stream of ~9 instructions per matrix instruction cannot fill the pipe alone.
+// Net 960 against 1070 TFLOP/s on cache-resident keys, so QT = 1 is what is launched.
 template <int D, int BM, int QT>
 __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_eu(2 / QT, 2 / QT)))
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
