@@ -3,15 +3,16 @@
 //   pool_kernel   : Q_hat, K_hat = mean over the real rows of each sub-block, an HBM stream.  The fp32
 //                   means (Q_hat already times 1/sqrt(d)) are stored split into three bf16 terms
 //                   x = hi + mid + lo, which together carry the 24 bits of the fp32 value.
-//   score_kernel  : S_hat[u,v] = sum over the r x r sub-block pairs of softmax(Q_hat K_hat^T / sqrt(d)).
-//                   The sub-block attention matrix A_hat is never stored: a work-group owns 128 query
-//                   sub-blocks (32 per wave) and walks all key sub-blocks twice (first pass: row maximum
-//                   and normaliser, second pass: normalised probabilities folded r x r), writing only the
-//                   block scores.  The logits run on the bf16 matrix cores as six partial products
-//                   hi.hi + hi.mid + mid.hi + hi.lo + lo.hi + mid.mid with fp32 accumulation: every
-//                   bf16 product is exact in fp32 and the dropped terms are below 2^-23 of the result, so
-//                   the logits are as accurate as an fp32 contraction at 2.7 times its speed (the mask
-//                   decision that follows stays an fp32 one).
+//   score_lse_kernel / score_fold_kernel : S_hat[u,v] = sum over the r x r sub-block pairs of
+//                   softmax(Q_hat K_hat^T / sqrt(d)).  The sub-block attention matrix A_hat is never stored.
+//                   One pass over the contraction: per (query sub-block, key block) the base-2 log of the
+//                   summed exponentials of the block's key sub-blocks (which needs no row reference) and per
+//                   query sub-block the row log-sum-exp; a second, memory-bound kernel turns these into
+//                   probabilities and folds the r query sub-blocks of a query block.  The logits run on the
+//                   bf16 matrix cores as six partial products hi.hi + hi.mid + mid.hi + hi.lo + lo.hi +
+//                   mid.mid with fp32 accumulation: every bf16 product is exact in fp32 and the dropped terms
+//                   are below 2^-23 of the result, so the logits are as accurate as an fp32 contraction at
+//                   several times its speed (the mask decision that follows stays an fp32 one).
 #include "common.h"
 
 namespace dfs {
@@ -101,37 +102,48 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
 
 // ------------------------------------------------------------------------------------ scoring
 
-// Running (max, sum of exp) of a softmax row; merge of two partial rows.
-__device__ __forceinline__ void online_add(float& m, float& z, float x) {
-  const float e = __expf(-fabsf(x - m));
-  if (x > m) { z = z * e + 1.f; m = x; } else { z += e; }
+constexpr float LSE_START = -1.0e30f;          // finite stand-in for "nothing seen yet" (keeps differences finite)
+
+// Running base-2 log-sum-exp (reference m, sum z of 2^(x - m)): add one term, merge two partial sums.
+__device__ __forceinline__ void lse_add(float& m, float& z, float x) {
+  const float mn = fmaxf(m, x);
+  z = z * __builtin_amdgcn_exp2f(m - mn) + __builtin_amdgcn_exp2f(x - mn);
+  m = mn;
 }
-__device__ __forceinline__ void online_merge(float& m, float& z, float m2, float z2) {
-  const float mx = fmaxf(m, m2);
-  if (mx == -INFINITY) { z = 0.f; return; }
-  z = z * __expf(m - mx) + z2 * __expf(m2 - mx);
-  m = mx;
+__device__ __forceinline__ void lse_merge(float& m, float& z, float m2, float z2) {
+  const float mn = fmaxf(m, m2);
+  z = z * __builtin_amdgcn_exp2f(m - mn) + z2 * __builtin_amdgcn_exp2f(m2 - mn);
+  m = mn;
 }
 
-template <int D>
+// Pass 1 (the contraction, once).  A work-group owns 128 query sub-blocks (32 per wave) and one of KSPLIT
+// ranges of key tiles (32 key sub-blocks each).  The logits are computed transposed, keys along the rows of
+// the matrix instruction's result, so that a lane holds, for ONE query sub-block (its column), runs of four
+// consecutive key sub-blocks: the R key sub-blocks of a key block fold inside the lane (R = 8: plus one
+// exchange between the two lane halves).  Per (query sub-block i, key block v) it stores
+//   T[v][i] = log2 sum over the key sub-blocks j of v of 2^logit(i, j)          (logits already in base 2)
+// which needs no row reference, and per query sub-block the log-sum-exp over its key range.  Pass 2 turns
+// T into probabilities and folds the R query sub-blocks of a query block.
+template <int D, int R>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-score_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, float* __restrict__ score, int M_s, int M_v,
-             int r, int n_live) {
+score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, float* __restrict__ tt,
+                 float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit) {
   constexpr int RS = 3 * D;                   // elements of a centroid row (hi, mid, lo planes)
   constexpr int RSP = RS + 8;                 // LDS row stride: 16 bytes of skew keep the row-per-lane reads conflict-free
   constexpr int KS = D / 16;                  // product steps of 16 features
   constexpr int CPT = 32 * RS / 8 / 256;      // 16-byte chunks of a key tile per thread (6 at d=128)
-  __shared__ __attribute__((aligned(16))) uint16_t s_k[32 * RSP];
-  __shared__ float s_p[4][32][33];
+  constexpr int G = R < 4 ? R : 4;            // key sub-blocks of one key block that sit in consecutive registers
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[2][32 * RSP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, half = lane >> 5;
   const int head = blockIdx.y;
-  const int i0 = blockIdx.x * 128 + wave * 32;   // first query sub-block of this wave
+  const int split = blockIdx.x % ksplit;
+  const int i0 = (blockIdx.x / ksplit) * 128 + wave * 32;   // first query sub-block of this wave
   const uint16_t* qh = q_hat + int64_t(head) * M_s * RS;
   const uint16_t* kh = k_hat + int64_t(head) * M_s * RS;
 
-  // Query centroids as the A operand: lane (n, half) holds row i0 + n, features 16 kk + 8 half .. + 7, three planes.
-  bf16x8 aq[3][KS];
+  // Query centroids as the B operand: lane (n, half) holds row i0 + n, features 16 kk + 8 half .. + 7, three planes.
+  bf16x8 bq[3][KS];
   {
     const int row = i0 + n;
 #pragma unroll
@@ -140,10 +152,12 @@ score_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_
       for (int kk = 0; kk < KS; ++kk) {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (row < M_s) v = *reinterpret_cast<const u32x4*>(qh + int64_t(row) * RS + p * D + 16 * kk + 8 * half);
-        aq[p][kk] = __builtin_bit_cast(bf16x8, v);
+        bq[p][kk] = __builtin_bit_cast(bf16x8, v);
       }
   }
   const int n_tiles = (n_live + 31) / 32;     // key sub-blocks at or beyond n_live are empty
+  const int t_begin = split * tiles_per_split;
+  const int t_end = t_begin + tiles_per_split < n_tiles ? t_begin + tiles_per_split : n_tiles;
 
   // key tile t (32 centroid rows, contiguous in memory) -> registers -> LDS
   u32x4 stage[CPT];
@@ -156,121 +170,197 @@ score_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_
       if (row < M_s) stage[i] = *reinterpret_cast<const u32x4*>(kh + int64_t(t) * 32 * RS + int64_t(c) * 8);
     }
   };
-  auto commit = [&]() {
+  auto commit = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
       const int c = tid + i * 256;
-      *reinterpret_cast<u32x4*>(&s_k[(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = stage[i];
+      *reinterpret_cast<u32x4*>(&s_k[buf][(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = stage[i];
     }
   };
-  // logits of the 32 x 32 tile: c[i] = <q_hat[row 8 (i/4) + 4 half + i%4], k_hat[column n]>
-  auto logit_tile = [&]() {
+  // transposed logits of the 32 x 32 tile: c[i] = <k_hat[row 8 (i/4) + 4 half + i%4 of the tile], q_hat[i0 + n]>
+  auto logit_tile = [&](int buf) {
     // three accumulators, so that consecutive matrix instructions never wait for each other's result
     f32x16 sa = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 sb = sa, big = sa;
-    const uint16_t* krow = &s_k[n * RSP + 8 * half];
+    const uint16_t* krow = &s_k[buf][n * RSP + 8 * half];
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
-      const bf16x8 bm = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
-      const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 2 * D + 16 * kk));
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[2][kk], bh, sa, 0, 0, 0);     // lo.hi
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bl, sb, 0, 0, 0);     // hi.lo
-      big = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bh, big, 0, 0, 0);   // hi.hi
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[1][kk], bm, sa, 0, 0, 0);     // mid.mid
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[1][kk], bh, sb, 0, 0, 0);     // mid.hi
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0][kk], bm, sa, 0, 0, 0);     // hi.mid
+      const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
+      const bf16x8 am = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
+      const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 2 * D + 16 * kk));
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[2][kk], sa, 0, 0, 0);     // hi.lo
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bq[0][kk], sb, 0, 0, 0);     // lo.hi
+      big = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[0][kk], big, 0, 0, 0);   // hi.hi
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bq[1][kk], sa, 0, 0, 0);     // mid.mid
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[1][kk], sb, 0, 0, 0);     // hi.mid
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bq[0][kk], sa, 0, 0, 0);     // mid.hi
     }
     const f32x16 small = sa + sb;
     return big + small;
   };
 
-  // pass 1: row maximum and normaliser.  Lane (n, half) holds rows 8 (i/4) + 4 half + i%4 of column n.
-  float m[16], z[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) { m[i] = -INFINITY; z[i] = 0.f; }
-  fetch(0);
-  for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();                          // every wave is done with the previous tile
-    commit();
+  float m_row = LSE_START, z_row = 0.f;       // this lane's share of the row log-sum-exp of query sub-block i0 + n
+  const int q_row = i0 + n;
+  float* tt_h = tt + int64_t(head) * M_v * M_s;
+  if (t_begin < t_end) {
+    fetch(t_begin);
+    commit(0);
     __syncthreads();
-    if (t + 1 < n_tiles) fetch(t + 1);
-    const f32x16 c = logit_tile();
-    if (t * 32 + n < n_live) {
+    for (int t = t_begin; t < t_end; ++t) {
+      const int buf = (t - t_begin) & 1;
+      if (t + 1 < t_end) fetch(t + 1);
+      f32x16 c = logit_tile(buf);
+      if (t + 1 < t_end) commit(buf ^ 1);     // the other buffer was last read before the previous barrier
+      if (t * 32 + 32 > n_live) {             // ragged end: key sub-blocks without rows count for nothing
 #pragma unroll
-      for (int i = 0; i < 16; ++i) online_add(m[i], z[i], c[i]);
+        for (int i = 0; i < 16; ++i)
+          if (t * 32 + 8 * (i / 4) + 4 * half + (i % 4) >= n_live) c[i] = -INFINITY;
+      }
+      // fold the key sub-blocks of each key block: groups of G consecutive registers
+#pragma unroll
+      for (int gi = 0; gi < 16 / G; ++gi) {
+        float mg = c[gi * G];
+#pragma unroll
+        for (int e = 1; e < G; ++e) mg = fmaxf(mg, c[gi * G + e]);
+        float sg = 0.f;
+        const float ref = mg == -INFINITY ? 0.f : mg;
+#pragma unroll
+        for (int e = 0; e < G; ++e) sg += __builtin_amdgcn_exp2f(c[gi * G + e] - ref);
+        float tv = mg == -INFINITY ? -INFINITY : mg + __builtin_amdgcn_logf(sg);
+        // key sub-block of the group's first register: 8 (first / 4) + 4 half + first % 4
+        const int first = gi * G;
+        const int ks = t * 32 + 8 * (first / 4) + 4 * half + (first % 4);
+        if (R == 8) {                          // the other half of the block sits in lane ^ 32
+          const float other = __shfl_xor(tv, 32, 64);
+          float m2 = fmaxf(tv, other);
+          tv = m2 == -INFINITY ? -INFINITY
+                               : m2 + __builtin_amdgcn_logf(__builtin_amdgcn_exp2f(tv - m2) + __builtin_amdgcn_exp2f(other - m2));
+        }
+        const int v = ks / R;
+        if ((R != 8 || half == 0) && v < M_v && q_row < M_s) tt_h[int64_t(v) * M_s + q_row] = tv;
+        if (R != 8 || half == 0) lse_add(m_row, z_row, tv);
+      }
+      __syncthreads();                        // tile t has been read by every wave; tile t + 1 is in LDS
     }
   }
-#pragma unroll
-  for (int off = 1; off < 32; off <<= 1) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float m2 = __shfl_xor(m[i], off, 64), z2 = __shfl_xor(z[i], off, 64);
-      online_merge(m[i], z[i], m2, z2);
-    }
+  // the two lane halves of a column hold different key blocks of the same query sub-block
+  {
+    const float m2 = __shfl_xor(m_row, 32, 64), z2 = __shfl_xor(z_row, 32, 64);
+    lse_merge(m_row, z_row, m2, z2);
   }
-  float rinv[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int row = i0 + 8 * (i / 4) + 4 * half + (i % 4);
-    rinv[i] = (row < n_live && z[i] > 0.f) ? 1.0f / z[i] : 0.f;   // empty query sub-blocks score nothing
-  }
+  if (half == 0 && q_row < M_s)
+    lse[(int64_t(head) * ksplit + split) * M_s + q_row] = z_row > 0.f ? m_row + __builtin_amdgcn_logf(z_row) : -INFINITY;
+}
 
-  // pass 2: probabilities, folded r x r into block scores
-  const int per = 32 / r;                     // blocks per tile edge
-  const int u0 = i0 / r;
+// Pass 2: S_hat[u][v] = sum over the R query sub-blocks i of u of 2^(T[v][i] - lse(i)), lse(i) merged over the
+// key ranges.  A work-group handles 32 query blocks x 32 key blocks; T is read along i (contiguous), the
+// scores are written along v (contiguous), the transposition goes through LDS.
+template <int R>
+__global__ void __launch_bounds__(256) score_fold_kernel(const float* __restrict__ tt, const float* __restrict__ lse,
+                                                         float* __restrict__ score, int M_s, int M_v, int n_live, int ksplit) {
+  __shared__ float s_t[32][33];
+  const int head = blockIdx.z, u0 = blockIdx.x * 32, v0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
+  const float* tt_h = tt + int64_t(head) * M_v * M_s;
+  const float* lse_h = lse + int64_t(head) * ksplit * M_s;
+  // row log-sum-exp of the R sub-blocks of query block u0 + tx
+  float l[R];
+#pragma unroll
+  for (int a = 0; a < R; ++a) {
+    const int i = (u0 + tx) * R + a;
+    float m = LSE_START, z = 0.f;
+    if (u0 + tx < M_v && i < n_live) {
+      for (int sp = 0; sp < ksplit; ++sp) lse_add(m, z, lse_h[int64_t(sp) * M_s + i]);
+    }
+    l[a] = z > 0.f ? m + __builtin_amdgcn_logf(z) : INFINITY;       // +inf: an empty query sub-block scores nothing
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int v = v0 + ty + 8 * k;
+    float acc = 0.f;
+    if (v < M_v && u0 + tx < M_v) {
+      const float* row = tt_h + int64_t(v) * M_s + int64_t(u0 + tx) * R;
+#pragma unroll
+      for (int a = 0; a < R; ++a) acc += __builtin_amdgcn_exp2f(row[a] - l[a]);
+    }
+    s_t[ty + 8 * k][tx] = acc;                                       // [v][u]
+  }
+  __syncthreads();
   float* out = score + int64_t(head) * M_v * M_v;
-  const int n_tiles_all = (M_s + 31) / 32;
-  fetch(0);
-  for (int t = 0; t < n_tiles_all; ++t) {
-    __syncthreads();
-    commit();
-    __syncthreads();
-    if (t + 1 < n_tiles_all) fetch(t + 1);
-    if (t < n_tiles) {
-      const f32x16 c = logit_tile();
-      const bool live = t * 32 + n < n_live;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s_p[wave][8 * (i / 4) + 4 * half + (i % 4)][n] = live ? __expf(c[i] - m[i]) * rinv[i] : 0.f;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_p[wave][8 * (i / 4) + 4 * half + (i % 4)][n] = 0.f;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // s_p[wave] is private to this wave: order its writes before its reads
-    __builtin_amdgcn_wave_barrier();
-    for (int o = lane; o < per * per; o += 64) {
-      const int ur = o / per, vc = o % per;
-      float acc = 0.f;
-      for (int a = 0; a < r; ++a)
-        for (int b = 0; b < r; ++b) acc += s_p[wave][ur * r + a][vc * r + b];
-      const int u = u0 + ur, v = t * per + vc;
-      if (u < M_v && v < M_v) out[int64_t(u) * M_v + v] = acc;
-    }
-    __builtin_amdgcn_wave_barrier();
+  for (int k = 0; k < 4; ++k) {
+    const int u = u0 + ty + 8 * k, v = v0 + tx;
+    if (u < M_v && v < M_v) out[int64_t(u) * M_v + v] = s_t[tx][ty + 8 * k];
   }
 }
 
+// Workspace: Q_hat, K_hat (three bf16 planes each), T [heads][M_v][M_s] fp32, row log-sum-exp
+// [heads][KSPLIT_MAX][M_s] fp32.
+constexpr int KSPLIT_MAX = 4;
+static size_t ws_hat_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t)); }
+static size_t ws_tt_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_v * s.M_s * sizeof(float)); }
+static size_t ws_lse_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * KSPLIT_MAX * s.M_s * sizeof(float)); }
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s) {
-  return 2 * align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t));
+  return 2 * ws_hat_bytes(g, s) + ws_tt_bytes(g, s) + ws_lse_bytes(g, s);
+}
+
+// Key ranges per query group: the split that wastes the least of the last round of work-groups
+// (512 work-groups of 4 waves are resident on the chip at two waves per SIMD).
+static int choose_ksplit(int64_t groups_times_heads, int n_tiles) {
+  int best = 1;
+  double best_cost = 1e300;
+  for (int k = 1; k <= KSPLIT_MAX; ++k) {
+    const int per = (n_tiles + k - 1) / k;
+    const int64_t wgs = groups_times_heads * k;
+    const int64_t rounds = (wgs + 511) / 512;
+    const double cost = double(rounds) * (per + 2);       // +2: prologue / epilogue of a work-group, in tile units
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = k; }
+  }
+  return best;
+}
+
+template <int D, int R>
+static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* q_hat, const uint16_t* k_hat, float* tt, float* lse,
+                         float* score, int n_live, hipStream_t st) {
+  const int groups = (s.M_s + 127) / 128, n_tiles = (n_live + 31) / 32;
+  const int ksplit = choose_ksplit(int64_t(groups) * g->heads, n_tiles);
+  const int per = (n_tiles + ksplit - 1) / ksplit;
+  score_lse_kernel<D, R><<<dim3(unsigned(groups * ksplit), unsigned(g->heads)), 256, 0, st>>>(q_hat, k_hat, tt, lse, s.M_s, s.M_v, n_live,
+                                                                                              per, ksplit);
+  const unsigned tb = unsigned((s.M_v + 31) / 32);
+  score_fold_kernel<R><<<dim3(tb, tb, unsigned(g->heads)), 256, 0, st>>>(tt, lse, score, s.M_s, s.M_v, n_live, ksplit);
 }
 
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm, float* score,
                     void* ws, const int32_t* q_index, hipStream_t st) {
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
-  const size_t half = align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t));
-  uint16_t* q_hat = static_cast<uint16_t*>(ws);
-  uint16_t* k_hat = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + half);
+  if ((s.M_v + 31) / 32 > 65535) return fail(DFS_ESHAPE, "M_v=%d is too large for the scoring grid", s.M_v);
+  char* base = static_cast<char*>(ws);
+  uint16_t* q_hat = reinterpret_cast<uint16_t*>(base);
+  uint16_t* k_hat = reinterpret_cast<uint16_t*>(base + ws_hat_bytes(g, s));
+  float* tt = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s));
+  float* lse = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s) + ws_tt_bytes(g, s));
   dim3 pg(unsigned((s.M_s + 3) / 4), unsigned(g->heads), 2);
   const bool bf = dtype == DFS_BF16;
-  const float scale = 1.0f / sqrtf(float(g->d));
+  // 1/sqrt(d) of Eq. 2 and the change to base 2 go into Q_hat, so that the logits come out of the contraction in base 2
+  const float scale = 1.4426950408889634f / sqrtf(float(g->d));
 #define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_index, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
   if (g->d == 64) { if (bf) POOL(true, 64); else POOL(false, 64); }
   else            { if (bf) POOL(true, 128); else POOL(false, 128); }
 #undef POOL
   const int n_live = int((s.N_v + g->Bs - 1) / g->Bs);
-  dim3 sg(unsigned((s.M_s + 127) / 128), unsigned(g->heads));
-  if (g->d == 64) score_kernel<64><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live);
-  else score_kernel<128><<<sg, 256, 0, st>>>(q_hat, k_hat, score, s.M_s, s.M_v, s.r, n_live);
+#define SCORE(DD, RR) launch_score<DD, RR>(g, s, q_hat, k_hat, tt, lse, score, n_live, st)
+#define SCORE_R(DD)                                                                 \
+  switch (s.r) {                                                                    \
+    case 1: SCORE(DD, 1); break;                                                    \
+    case 2: SCORE(DD, 2); break;                                                    \
+    case 4: SCORE(DD, 4); break;                                                    \
+    case 8: SCORE(DD, 8); break;                                                    \
+    default: return fail(DFS_ESHAPE, "B/Bs=%d is not 1, 2, 4 or 8", s.r);           \
+  }
+  if (g->d == 64) { SCORE_R(64) } else { SCORE_R(128) }
+#undef SCORE_R
+#undef SCORE
   return launch_status("dfs_block_score");
 }
 
