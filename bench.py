@@ -114,10 +114,11 @@ def main():
         P.dfs_hilbert_perm(g, perm_pad, inv, blk_valid, ws); mark(1)
         if not fused:
             P.dfs_permute(g, dt, qd, perm_pad, qp)
-        P.dfs_permute(g, dt, kd, perm_pad, kp)
+        if not fused:
+            P.dfs_permute(g, dt, kd, perm_pad, kp)
         P.dfs_permute(g, dt, vd, perm_pad, vp); mark(2)
-        if fused:
-            P.dfs_block_score_src(g, dt, qd, perm_pad, kp, score, ws); mark(3)
+        if fused:       # the pooling kernel reorders K on the way
+            P.dfs_block_score_fused(g, dt, qd, kd, perm_pad, kp, score, ws); mark(3)
         else:
             P.dfs_block_score(g, dt, qp, kp, score, ws); mark(3)
         P.dfs_select_mask(g, score, P.DFS_SELECT_TOPK, a.sparsity, 0.0, None, kv_idx, kv_cnt, K_max, None, ws); mark(4)
@@ -165,7 +166,7 @@ def main():
     flop_dense = 4.0 * float(sz["N"]) ** 2 * w.d * w.heads
     attn_ms = stage_ms["sparse_attn"]
     e = 2 if w.dtype == "bf16" else 4
-    n_perm = 2 if fused else 3
+    n_perm = 1 if fused else 3
     bytes_permute = n_perm * w.heads * (sz["N"] + N_pad) * w.d * e + n_perm * N_pad * 4
     bytes_unperm = 2 * w.heads * sz["N"] * w.d * e + sz["N"] * 4
     if a.traffic_kib is not None:
@@ -233,11 +234,12 @@ def schedule_bench(a, P, w, sz, g, dt, qd, kd, vd, gen_s):
     def one(t, evs):
         qb, kb = qf.to(torch.bfloat16), kf.to(torch.bfloat16)
         evs[0].record()
-        P.dfs_permute(g, dt, kb, perm_pad, kp)
+        if t % w.delta != 0:
+            P.dfs_permute(g, dt, kb, perm_pad, kp)
         P.dfs_permute(g, dt, vd, perm_pad, vp)
         evs[1].record()
         if t % w.delta == 0:
-            P.dfs_block_score_src(g, dt, qb, perm_pad, kp, score, ws)
+            P.dfs_block_score_fused(g, dt, qb, kb, perm_pad, kp, score, ws)
             P.dfs_select_mask(g, score, P.DFS_SELECT_MASS_HEAD, w.cap, w.mass, None, kv_idx, kv_cnt, K_max, k_head, ws)
         evs[2].record()
         P.dfs_sparse_attn_fwd_src(g, dt, qb, perm_pad, kp, vp, kv_idx, kv_cnt, K_max, scale, o, None)

@@ -192,6 +192,12 @@ int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const 
  */
 int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
                         float* score, void* ws, size_t ws_bytes, void* stream);
+/* As dfs_block_score_src, but K comes in source order as well: the pooling kernel gathers its rows through the
+ * permutation and writes them out in the reordered layout on the way, so the call also does the work of
+ * dfs_permute for K (pads as zeros, text rows included; k_perm [heads, N_pad, d] out, bit-identical to
+ * dfs_permute) and a step that refreshes the mask reorders only V in a pass of its own.  k_perm must not alias k. */
+int dfs_block_score_fused(const dfs_geom* g, int dtype, const void* q, const void* k, const int32_t* perm_pad,
+                          void* k_perm, float* score, void* ws, size_t ws_bytes, void* stream);
 int dfs_sparse_attn_fwd_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
                             const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max, float scale,
                             void* o, float* lse, void* stream);

@@ -73,6 +73,7 @@ def _load():
         "dfs_sparse_attn_fwd": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]),
         "dfs_unperm": (C.c_int, [gp, C.c_int, vp, vp, vp, vp]),
         "dfs_block_score_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, sz, vp]),
+        "dfs_block_score_fused": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, vp, sz, vp]),
         "dfs_sparse_attn_fwd_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]),
         "dfs_attn_clock_probe": (C.c_int, [vp]),
         "dfs_forward": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, dbl, dbl,
@@ -87,7 +88,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
            "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
-           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe")
+           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused")
 DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
 
@@ -221,6 +222,16 @@ def dfs_block_score_src(g: Geom, dtype: int, q, perm_pad, k_perm, score, ws):
                                     _ptr(perm_pad, torch.int32, s.N_pad, "perm_pad"),
                                     _ptr(k_perm, td, g.heads * s.N_pad * g.d, "k_perm"),
                                     _ptr(score, torch.float32, g.heads * s.M_v * s.M_v, "score"), wp, wb, _stream()))
+
+
+def dfs_block_score_fused(g: Geom, dtype: int, q, k, perm_pad, k_perm, score, ws):
+    s = dfs_geom_sizes(g)
+    td = _torch_dtype(dtype)
+    wp, wb = _ws_args(ws)
+    _check(_lib.dfs_block_score_fused(C.byref(g), dtype, _ptr(q, td, g.heads * s.N * g.d, "q"), _ptr(k, td, g.heads * s.N * g.d, "k"),
+                                      _ptr(perm_pad, torch.int32, s.N_pad, "perm_pad"),
+                                      _ptr(k_perm, td, g.heads * s.N_pad * g.d, "k_perm"),
+                                      _ptr(score, torch.float32, g.heads * s.M_v * s.M_v, "score"), wp, wb, _stream()))
 
 
 def dfs_sparse_attn_fwd_src(g: Geom, dtype: int, q, perm_pad, k_perm, v_perm, kv_idx, kv_cnt, K_max: int, scale: float, o,

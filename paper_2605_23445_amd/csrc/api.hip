@@ -126,11 +126,16 @@ int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, cons
   const void* q_in = fused ? q : base + L.qp;
   void* o_out = fused ? o : base + L.op;
   if (!fused && (rc = run_permute(g, s, dtype, q, perm_pad, base + L.qp, hs))) return rc;
-  if ((rc = run_permute(g, s, dtype, k, perm_pad, base + L.kp, hs))) return rc;
+  // On a refresh step of the bf16 path the pooling kernel reorders K on the way (it reads K in source order
+  // and writes K'), which spares that reorder pass too.
+  const bool k_in_pool = fused && refresh;
+  if (!k_in_pool && (rc = run_permute(g, s, dtype, k, perm_pad, base + L.kp, hs))) return rc;
   if ((rc = run_permute(g, s, dtype, v, perm_pad, base + L.vp, hs))) return rc;
   if (refresh) {
     float* score = reinterpret_cast<float*>(base + L.score);
-    if ((rc = run_block_score(g, s, dtype, q_in, base + L.kp, score, base + L.sub, index, hs))) return rc;
+    if ((rc = run_block_score(g, s, dtype, q_in, k_in_pool ? k : static_cast<const void*>(base + L.kp), score, base + L.sub, index,
+                              k_in_pool ? base + L.kp : nullptr, hs)))
+      return rc;
     if ((rc = run_select_mask(g, s, score, mode, sparsity, mass, st->mask, st->kv_idx, st->kv_cnt, st->K_max,
                               st->k_head, base + L.sub, hs)))
       return rc;

@@ -23,7 +23,7 @@ int run_permute(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* x,
                 void* x_perm, hipStream_t st);
 // q_index (may be NULL): the permutation; Q is then read in source order and gathered while pooling.
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm,
-                    float* score, void* ws, const int32_t* q_index, hipStream_t st);
+                    float* score, void* ws, const int32_t* q_index, void* k_out, hipStream_t st);
 int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, int mode, double sparsity,
                     double mass, uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max,
                     int32_t* k_head, void* ws, hipStream_t st);

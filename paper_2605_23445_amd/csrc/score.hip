@@ -40,14 +40,18 @@ __device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uin
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_perm, const void* __restrict__ k_perm,
                                                    uint16_t* __restrict__ q_hat, uint16_t* __restrict__ k_hat,
-                                                   const int32_t* __restrict__ q_index, int64_t N_src, int64_t N_pad, int64_t N_v, int Bs,
-                                                   int M_s, float q_scale) {
+                                                   const int32_t* __restrict__ q_index, void* __restrict__ k_out, int64_t N_src,
+                                                   int64_t N_pad, int64_t N_v, int Bs, int M_s, float q_scale) {
   constexpr int EPL = BF16 ? 8 : 4;           // elements per lane (16 bytes)
   constexpr int TPR = D / EPL;                // lanes per row
   constexpr int RPP = 64 / TPR;               // rows per pass
   const int lane = threadIdx.x & 63;
   const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (s >= M_s) return;
+  // With k_out the key rows come in source order too: they are gathered through the permutation, pooled, and
+  // written out in the reordered layout on the way (pads as zeros), which spares the reorder pass of K.  The
+  // sub-blocks behind the video segment (text rows) are then copied only.
+  const bool k_copy = blockIdx.z == 1 && k_out != nullptr;
+  if (s >= M_s && !(k_copy && int64_t(s) * Bs < N_pad)) return;
   const int head = blockIdx.y;
   const void* src = blockIdx.z == 0 ? q_perm : k_perm;
   uint16_t* dst = blockIdx.z == 0 ? q_hat : k_hat;
@@ -60,15 +64,22 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
   // With q_index (the permutation) the query rows are gathered from the tensor in source order, which spares
   // the reorder pass of Q.
-  const bool gather = blockIdx.z == 0 && q_index != nullptr;
+  const bool gather = q_index != nullptr && (blockIdx.z == 0 || k_copy);
   const u32x4* base = reinterpret_cast<const u32x4*>(src) + (gather ? int64_t(head) * N_src * TPR : (int64_t(head) * N_pad + row0) * TPR) + c;
-  for (int i = rg; i < cnt; i += RPP) {
+  u32x4* copy = k_copy ? reinterpret_cast<u32x4*>(k_out) + (int64_t(head) * N_pad + row0) * TPR + c : nullptr;
+  const int rows = k_copy ? Bs : cnt;         // a copy covers the pad rows of the sub-block as well
+  for (int i = rg; i < rows; i += RPP) {
     int64_t from = i;
+    bool real = true;
     if (gather) {
       from = q_index[row0 + i];
-      if (from < 0 || from >= N_src) continue;
+      real = from >= 0 && from < N_src;
     }
-    const u32x4 v = __builtin_nontemporal_load(base + from * TPR);
+    if (!real && !k_copy) continue;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (real) v = __builtin_nontemporal_load(base + from * TPR);
+    if (k_copy) __builtin_nontemporal_store(v, copy + int64_t(i) * TPR);
+    if (!real || i >= cnt) continue;
     if (BF16) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -80,6 +91,7 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
       for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(v[e]);
     }
   }
+  if (s >= M_s) return;                        // copied only
 #pragma unroll
   for (int off = TPR; off < 64; off <<= 1) {
 #pragma unroll
@@ -332,7 +344,7 @@ static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* 
 }
 
 int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void* q_perm, const void* k_perm, float* score,
-                    void* ws, const int32_t* q_index, hipStream_t st) {
+                    void* ws, const int32_t* q_index, void* k_out, hipStream_t st) {
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
   if ((s.M_v + 31) / 32 > 65535) return fail(DFS_ESHAPE, "M_v=%d is too large for the scoring grid", s.M_v);
   char* base = static_cast<char*>(ws);
@@ -340,11 +352,12 @@ int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   uint16_t* k_hat = reinterpret_cast<uint16_t*>(base + ws_hat_bytes(g, s));
   float* tt = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s));
   float* lse = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s) + ws_tt_bytes(g, s));
-  dim3 pg(unsigned((s.M_s + 3) / 4), unsigned(g->heads), 2);
+  const int64_t pool_subs = k_out ? s.N_pad / g->Bs : s.M_s;   // with k_out the text blocks are copied as well
+  dim3 pg(unsigned((pool_subs + 3) / 4), unsigned(g->heads), 2);
   const bool bf = dtype == DFS_BF16;
   // 1/sqrt(d) of Eq. 2 and the change to base 2 go into Q_hat, so that the logits come out of the contraction in base 2
   const float scale = 1.4426950408889634f / sqrtf(float(g->d));
-#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_index, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
+#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_index, k_out, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
   if (g->d == 64) { if (bf) POOL(true, 64); else POOL(false, 64); }
   else            { if (bf) POOL(true, 128); else POOL(false, 128); }
 #undef POOL
@@ -378,7 +391,7 @@ extern "C" int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm,
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
     return fail(DFS_EWORKSPACE, "dfs_block_score: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
-  return run_block_score(g, s, dtype, q_perm, k_perm, score, ws, nullptr, as_stream(stream));
+  return run_block_score(g, s, dtype, q_perm, k_perm, score, ws, nullptr, nullptr, as_stream(stream));
 }
 
 extern "C" int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, const int32_t* perm_pad, const void* k_perm,
@@ -391,5 +404,19 @@ extern "C" int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, 
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
     return fail(DFS_EWORKSPACE, "dfs_block_score_src: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
-  return run_block_score(g, s, dtype, q, k_perm, score, ws, perm_pad, as_stream(stream));
+  return run_block_score(g, s, dtype, q, k_perm, score, ws, perm_pad, nullptr, as_stream(stream));
+}
+
+extern "C" int dfs_block_score_fused(const dfs_geom* g, int dtype, const void* q, const void* k, const int32_t* perm_pad,
+                                     void* k_perm, float* score, void* ws, size_t ws_bytes, void* stream) {
+  dfs_sizes s;
+  int rc = check_geom(g, &s);
+  if (rc) return rc;
+  if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_block_score_fused: bf16 tensors only");
+  if (!q || !k || !perm_pad || !k_perm || !score) return fail(DFS_EINVAL, "dfs_block_score_fused: NULL argument");
+  if (k == k_perm) return fail(DFS_EINVAL, "dfs_block_score_fused: k_perm must not alias k");
+  const size_t need = ws_block_score(g, s);
+  if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
+    return fail(DFS_EWORKSPACE, "dfs_block_score_fused: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
+  return run_block_score(g, s, dtype, q, k, score, ws, perm_pad, k_perm, as_stream(stream));
 }

@@ -450,6 +450,12 @@ def test_source_order_variants_are_bit_identical(w):
     score2 = torch.full_like(score, float("nan"))
     P.dfs_block_score_src(g, dt, qd, perm_pad, kp, score2, G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_BLOCK_SCORE)))
     assert torch.equal(score.view(torch.int32), score2.view(torch.int32))
+    # K in source order as well: the call reorders it on the way (pads zero, text rows included)
+    score3 = torch.full_like(score, float("nan"))
+    kp3 = torch.full_like(kp, float("nan"))
+    P.dfs_block_score_fused(g, dt, qd, kd, perm_pad, kp3, score3, G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_BLOCK_SCORE)))
+    assert torch.equal(kp.view(torch.int16), kp3.view(torch.int16))
+    assert torch.equal(score.view(torch.int32), score3.view(torch.int32))
     st = G.gpu_select(g, score, P.DFS_SELECT_TOPK, w.sparsity[0])
     o_perm, lse = G.gpu_attn(g, dt, qp, kp, vp, st)
     o_ref = G.gpu_unperm(g, dt, o_perm, inv)
