@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 # HBM-side traffic of the attention kernel per launch on the default workload (wan, sparsity 0.9), from
 # profiles/wan90_attention_counters.txt: FETCH_SIZE x 2.00 and WRITE_SIZE x 1.00, in bytes.
-RECORDED_TRAFFIC = {("wan", 0.9): (29936000 * 1024 * 2.0, 756903 * 1024 * 1.0)}
+RECORDED_TRAFFIC = {("wan", 0.9): (30326000 * 1024 * 2.0, 756902 * 1024 * 1.0)}
 
 
 def parse():
