@@ -137,6 +137,24 @@ def test_score_and_select_small(w):
     assert np.array_equal(st.kv_cnt.cpu().numpy()[:, :sz["M_v"]], k_row_o + sz["M_x"])
 
 
+@pytest.mark.parametrize("T,H,W,Bs", [(4, 48, 48, 32), (6, 32, 64, 32), (5, 40, 50, 16)])
+def test_score_key_range_splits(T, H, W, Bs):
+    """Scoring on shapes where one head's work is split over three and four key ranges per query group
+    (few work-groups, 9 to 20 key tiles), with a ragged last tile: scores against the fp64 oracle."""
+    w = Workload(f"split_{T}x{H}x{W}", T, H, W, heads=2, d=64, dtype="bf16", B=128, Bs=Bs, sparsity=(0.8,), seed=123)
+    sz = derived_sizes(w)
+    say(f"score splits {w.name}: M_s {sz['M_s']}")
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v, perm_pad_o, _, _ = _oracle_inputs(w)
+    perm_pad, _, _ = G.gpu_perm(g)
+    qp, kp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k))
+    score_np = G.gpu_score(g, dt, qp, kp).cpu().numpy()
+    want = O.block_score(O.permute(as_f64(q), perm_pad_o), O.permute(as_f64(k), perm_pad_o), sz["N_v"], w.B, w.Bs)
+    err = np.abs(score_np - want).max()
+    say(f"  score max err {err:.3e} (tol {SCORE_TOL * sz['r']:.1e})")
+    assert err <= SCORE_TOL * sz["r"]
+
+
 def test_select_ties_and_edge_rows():
     """Rows built by hand on the host: exact ties, negative and signed-zero scores, a full-keep row."""
     M_v = 200
