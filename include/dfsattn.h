@@ -134,7 +134,8 @@ int dfs_permute(const dfs_geom* g, int dtype, const void* x, const int32_t* perm
  * Text blocks are not scored.  Means, softmax and sums are fp32; the logits run on the bf16 matrix cores
  * over an exact three-term split of the fp32 means (as accurate as an fp32 contraction).
  *   q_perm, k_perm [heads, N_pad, d] in (`dtype`);  score [heads, M_v, M_v] out, fp32.
- * ws: DFS_WS_BLOCK_SCORE.
+ * ws: DFS_WS_BLOCK_SCORE (the pooled means and an fp32 array of heads x M_v x M_s partial log-sums:
+ * 0.4 GB at 75 600 tokens x 40 heads).
  */
 int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
                     float* score, void* ws, size_t ws_bytes, void* stream);
