@@ -101,3 +101,28 @@ def test_schedule_matches_oracle_and_rejects_bad_steps():
     for bad in ((0, 0, 1), (10, 10, 1), (10, -1, 1), (10, 3, 0)):
         with pytest.raises(P.DfsError):
             P.dfs_schedule(*bad)
+
+
+def test_build_entry_does_not_need_a_built_library():
+    """build() must work in a tree where the library does not exist yet: it may not import the package
+    (whose import fails loudly without the library) before it has built it."""
+    import ast
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    tree = ast.parse(open(os.path.join(root, "__graft_entry__.py")).read())
+    build = next(n for n in tree.body if isinstance(n, ast.FunctionDef) and n.name == "build")
+    seen_build_call = False
+    for node in ast.walk(build):
+        if isinstance(node, ast.Call) and isinstance(node.func, ast.Attribute) and node.func.attr == "build_library":
+            seen_build_call = True
+    assert seen_build_call
+    first_pkg_import = min((n.lineno for n in ast.walk(build)
+                            if isinstance(n, (ast.Import, ast.ImportFrom))
+                            and any("paper_2605_23445_amd" in (a.name if isinstance(n, ast.Import) else (n.module or "")) for a in n.names)),
+                           default=None)
+    call_line = next(n.lineno for n in ast.walk(build)
+                     if isinstance(n, ast.Call) and isinstance(n.func, ast.Attribute) and n.func.attr == "build_library")
+    assert first_pkg_import is None or first_pkg_import > call_line
+    # and build.py itself imports nothing from the package
+    src = open(os.path.join(root, "paper_2605_23445_amd", "build.py")).read()
+    assert "paper_2605_23445_amd" not in src.replace("paper_2605_23445_amd/build.py", "")
