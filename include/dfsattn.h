@@ -19,7 +19,8 @@
  *   - Return value: DFS_OK or a negative dfs_status.  Arguments are checked on the host
  *     before anything is launched; after an error dfs_last_error() describes it.  A scratch
  *     buffer `ws` must hold at least dfs_workspace_bytes() bytes and be 256-byte aligned;
- *     its contents are undefined afterwards.
+ *     its contents are undefined afterwards.  Q/K/V/O tensors must be 16-byte aligned (rows move
+ *     16 bytes at a time), index, count, score and lse arrays 4-byte aligned: DFS_EINVAL otherwise.
  */
 #ifndef DFSATTN_H
 #define DFSATTN_H

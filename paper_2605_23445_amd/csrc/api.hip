@@ -113,6 +113,8 @@ int dfs_forward(const dfs_geom* g, int dtype, const void* q, const void* k, cons
   if (rc) return rc;
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!q || !k || !v || !o || !perm_pad || !inv || !st) return fail(DFS_EINVAL, "dfs_forward: NULL argument");
+  if (misaligned(16, {q, k, v, o}) || misaligned(4, {perm_pad, inv, st->kv_idx, st->kv_cnt, st->k_head}))
+    return fail(DFS_EINVAL, "dfs_forward: tensors must be 16-byte aligned, index arrays 4-byte aligned");
   if (!st->kv_idx || !st->kv_cnt) return fail(DFS_EINVAL, "dfs_forward: mask state has no kv_idx/kv_cnt");
   FwdLayout L = forward_layout(g, s, dtype);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < L.total)

@@ -619,6 +619,8 @@ extern "C" int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_p
   if (rc) return rc;
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!q_perm || !k_perm || !v_perm || !kv_idx || !kv_cnt || !o_perm) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd: NULL argument");
+  if (misaligned(16, {q_perm, k_perm, v_perm, o_perm}) || misaligned(4, {kv_idx, kv_cnt, lse}))
+    return fail(DFS_EINVAL, "dfs_sparse_attn_fwd: tensors must be 16-byte aligned, index and fp32 arrays 4-byte aligned");
   if (!(scale > 0.f)) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd: scale must be positive");
   return run_sparse_attn(g, s, dtype, q_perm, k_perm, v_perm, kv_idx, kv_cnt, K_max, scale, o_perm, lse, nullptr, as_stream(stream));
 }
@@ -631,6 +633,8 @@ extern "C" int dfs_sparse_attn_fwd_src(const dfs_geom* g, int dtype, const void*
   if (rc) return rc;
   if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_sparse_attn_fwd_src: bf16 tensors only");
   if (!q || !perm_pad || !k_perm || !v_perm || !kv_idx || !kv_cnt || !o) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd_src: NULL argument");
+  if (misaligned(16, {q, k_perm, v_perm, o}) || misaligned(4, {perm_pad, kv_idx, kv_cnt, lse}))
+    return fail(DFS_EINVAL, "dfs_sparse_attn_fwd_src: tensors must be 16-byte aligned, index and fp32 arrays 4-byte aligned");
   if (!(scale > 0.f)) return fail(DFS_EINVAL, "dfs_sparse_attn_fwd_src: scale must be positive");
   return run_sparse_attn(g, s, dtype, q, k_perm, v_perm, kv_idx, kv_cnt, K_max, scale, o, lse, perm_pad, as_stream(stream));
 }

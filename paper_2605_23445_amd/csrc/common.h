@@ -1,5 +1,6 @@
 // Internal helpers shared by the HIP translation units of libdfsattn (not part of the ABI).
 #pragma once
+#include <initializer_list>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -16,6 +17,13 @@ int launch_status(const char* what);
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+// Tensor rows move 16 bytes at a time, so every Q/K/V/O tensor must start on a 16-byte boundary
+// (index, count and fp32 arrays on a 4-byte boundary).  True if any of the pointers does not.
+inline bool misaligned(size_t a, std::initializer_list<const void*> ps) {
+  for (const void* p : ps)
+    if (reinterpret_cast<uintptr_t>(p) & (a - 1)) return true;
+  return false;
+}
 inline int elem_size(int dtype) { return dtype == DFS_BF16 ? 2 : 4; }
 
 // Stage entry points without argument checks, used by dfs_forward after it has validated once.

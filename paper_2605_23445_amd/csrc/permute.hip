@@ -76,6 +76,7 @@ extern "C" int dfs_permute(const dfs_geom* g, int dtype, const void* x, const in
   if (rc) return rc;
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!x || !perm_pad || !x_perm) return fail(DFS_EINVAL, "dfs_permute: NULL argument");
+  if (misaligned(16, {x, x_perm}) || misaligned(4, {perm_pad})) return fail(DFS_EINVAL, "dfs_permute: tensors must be 16-byte aligned, the index array 4-byte aligned");
   return run_permute(g, s, dtype, x, perm_pad, x_perm, as_stream(stream));
 }
 
@@ -85,5 +86,6 @@ extern "C" int dfs_unperm(const dfs_geom* g, int dtype, const void* o_perm, cons
   if (rc) return rc;
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!o_perm || !inv || !o) return fail(DFS_EINVAL, "dfs_unperm: NULL argument");
+  if (misaligned(16, {o_perm, o}) || misaligned(4, {inv})) return fail(DFS_EINVAL, "dfs_unperm: tensors must be 16-byte aligned, the index array 4-byte aligned");
   return run_unperm(g, s, dtype, o_perm, inv, o, as_stream(stream));
 }

@@ -388,6 +388,7 @@ extern "C" int dfs_block_score(const dfs_geom* g, int dtype, const void* q_perm,
   if (rc) return rc;
   if (dtype != DFS_F32 && dtype != DFS_BF16) return fail(DFS_EDTYPE, "dtype %d is not DFS_F32 or DFS_BF16", dtype);
   if (!q_perm || !k_perm || !score) return fail(DFS_EINVAL, "dfs_block_score: NULL argument");
+  if (misaligned(16, {q_perm, k_perm}) || misaligned(4, {score})) return fail(DFS_EINVAL, "dfs_block_score: tensors must be 16-byte aligned, the score array 4-byte aligned");
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
     return fail(DFS_EWORKSPACE, "dfs_block_score: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
@@ -401,6 +402,8 @@ extern "C" int dfs_block_score_src(const dfs_geom* g, int dtype, const void* q, 
   if (rc) return rc;
   if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_block_score_src: bf16 tensors only");
   if (!q || !perm_pad || !k_perm || !score) return fail(DFS_EINVAL, "dfs_block_score_src: NULL argument");
+  if (misaligned(16, {q, k_perm}) || misaligned(4, {perm_pad, score}))
+    return fail(DFS_EINVAL, "dfs_block_score_src: tensors must be 16-byte aligned, index and score arrays 4-byte aligned");
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)
     return fail(DFS_EWORKSPACE, "dfs_block_score_src: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);
@@ -414,6 +417,8 @@ extern "C" int dfs_block_score_fused(const dfs_geom* g, int dtype, const void* q
   if (rc) return rc;
   if (dtype != DFS_BF16) return fail(DFS_EDTYPE, "dfs_block_score_fused: bf16 tensors only");
   if (!q || !k || !perm_pad || !k_perm || !score) return fail(DFS_EINVAL, "dfs_block_score_fused: NULL argument");
+  if (misaligned(16, {q, k, k_perm}) || misaligned(4, {perm_pad, score}))
+    return fail(DFS_EINVAL, "dfs_block_score_fused: tensors must be 16-byte aligned, index and score arrays 4-byte aligned");
   if (k == k_perm) return fail(DFS_EINVAL, "dfs_block_score_fused: k_perm must not alias k");
   const size_t need = ws_block_score(g, s);
   if (!ws || (uintptr_t(ws) & 255) || ws_bytes < need)

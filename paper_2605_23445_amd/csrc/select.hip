@@ -215,6 +215,7 @@ extern "C" int dfs_select_mask(const dfs_geom* g, const float* score, int mode, 
   int rc = check_geom(g, &s);
   if (rc) return rc;
   if (!score || !kv_idx || !kv_cnt) return fail(DFS_EINVAL, "dfs_select_mask: NULL argument");
+  if (misaligned(4, {score, kv_idx, kv_cnt, k_head})) return fail(DFS_EINVAL, "dfs_select_mask: score, list and count arrays must be 4-byte aligned");
   const size_t need = ws_select_mask(g, s);
   if ((mode == DFS_SELECT_MASS_HEAD || mode == DFS_SELECT_MASS_ROW) && (!ws || (uintptr_t(ws) & 255) || ws_bytes < need))
     return fail(DFS_EWORKSPACE, "dfs_select_mask: workspace of %zu bytes needed (256-byte aligned), got %zu", need, ws_bytes);

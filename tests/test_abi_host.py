@@ -80,6 +80,14 @@ def test_argument_errors_come_before_any_launch():
     assert lib.dfs_sparse_attn_fwd(C.byref(g), 1, fake, fake, None, fake, fake, 2, 0.125, fake, None, None) == -1
     lib.dfs_block_score.argtypes = [C.POINTER(P.Geom), C.c_int, vp, vp, vp, vp, C.c_size_t, vp]
     assert lib.dfs_block_score(C.byref(g), 0, fake, fake, fake, None, 0, None) == -4
+    # tensors that do not start on a 16-byte boundary (index arrays: 4-byte) are refused, not read
+    odd8, odd2 = C.c_void_p(0x1008), C.c_void_p(0x1002)
+    assert lib.dfs_permute(C.byref(g), 0, odd8, fake, fake, None) == -1
+    assert b"aligned" in lib.dfs_last_error()
+    assert lib.dfs_permute(C.byref(g), 0, fake, odd2, fake, None) == -1
+    assert lib.dfs_sparse_attn_fwd(C.byref(g), 1, fake, odd8, fake, fake, fake, 2, 0.125, fake, None, None) == -1
+    assert lib.dfs_sparse_attn_fwd(C.byref(g), 1, fake, fake, fake, fake, fake, 2, 0.125, fake, odd2, None) == -1
+    assert lib.dfs_block_score(C.byref(g), 0, fake, odd8, fake, fake, 1 << 30, None) == -1
 
 
 def test_binding_refuses_host_tensors():
