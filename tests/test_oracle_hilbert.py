@@ -80,7 +80,7 @@ def _fnv1a64(data: bytes) -> str:
     return "%016x" % h
 
 
-def test_config_grids_match_survey_pins():
+def test_config_grids_match_recorded_digests():
     _, _, perms = _gold()
     for (T, H, W), first, last, digest in perms:
         perm_pad, _, _ = O.hilbert_perm(T, H, W, 0, 128)
