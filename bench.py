@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--keep-all", action="store_true", help="keep every key block: the same kernels as a dense attention (in-house dense time)")
     ap.add_argument("--heads", type=int, default=0, help="override the head count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark: measure what the chip sustains on bare matrix-instruction chains and on a "
+                         "plain copy (one JSON line), to set beside the nominal peaks")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the warm-up (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
@@ -60,6 +63,8 @@ def main():
 
     import paper_2605_23445_amd as P
     from workloads import CONFIGS, derived_sizes, make_qkv
+    if a.probe:
+        return probe_rates(P, torch)
 
     w = CONFIGS[a.workload]
     if a.heads:
@@ -204,6 +209,38 @@ def main():
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, sz, a.sparsity, q, k, v, flop_dense)
+    print(json.dumps(out))
+
+
+def probe_rates(P, torch):
+    """Sustained rates of the chip: matrix-instruction chains at one and two waves per SIMD, and a 1 GiB copy."""
+    torch.cuda.set_device(0)
+    out = {"probe": "MI355X sustained rates", "nominal": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for waves_per_simd in (1, 2):
+        wgs, iters = 256 * waves_per_simd, 20000
+        sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+        counters = torch.zeros(2, dtype=torch.int64, device="cuda")
+        P.dfs_probe_mfma(wgs, 100, sink, None)
+        torch.cuda.synchronize()
+        e0.record(); P.dfs_probe_mfma(wgs, iters, sink, counters); e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        c = counters.cpu().numpy().astype(float)
+        flop = wgs * 4.0 * iters * 4.0 * 32 * 32 * 16 * 2
+        out[f"mfma_chain_{waves_per_simd}_wave_per_simd"] = {"tflops": flop / ms * 1e-9, "ms": ms,
+                                                             "shader_clock_mhz": c[0] / c[1] * 100.0 if c[1] else None}
+    src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    P.dfs_probe_copy(src, dst)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        P.dfs_probe_copy(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    out["copy_1GiB"] = {"gbs_read_plus_write": 2.0 * (1 << 30) / ms * 1e-6, "ms": ms}
     print(json.dumps(out))
 
 

@@ -263,6 +263,17 @@ int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_ke
  */
 int dfs_attn_clock_probe(uint64_t* counters);
 
+/*
+ * Measurement probes, not part of the method: what the chip sustains, to set beside the nominal peaks.
+ * dfs_probe_mfma launches `work_groups` x 4 waves that run `iters` x 4 independent v_mfma_f32_32x32x16_bf16
+ * (32768 flop each per wave) and nothing else; sink [work_groups * 256] fp32 out (device);
+ * counters (device, 2 x uint64, zeroed by the caller, or NULL) receives work-group 0's shader-clock cycles and
+ * 100 MHz ticks.  dfs_probe_copy copies `bytes` (a multiple of 16, 16-byte aligned device pointers) with
+ * 16 bytes per lane.  Time them with events on `stream`.
+ */
+int dfs_probe_mfma(int32_t work_groups, int32_t iters, float* sink, uint64_t* counters, void* stream);
+int dfs_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,6 +76,8 @@ def _load():
         "dfs_block_score_fused": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, vp, sz, vp]),
         "dfs_sparse_attn_fwd_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]),
         "dfs_attn_clock_probe": (C.c_int, [vp]),
+        "dfs_probe_mfma": (C.c_int, [i32, i32, vp, vp, vp]),
+        "dfs_probe_copy": (C.c_int, [vp, vp, sz, vp]),
         "dfs_forward": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, dbl, dbl,
                                   C.POINTER(_MaskStateC), f32, vp, vp, sz, vp]),
     }
@@ -88,7 +90,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
            "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
-           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused")
+           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused", "dfs_probe_mfma", "dfs_probe_copy")
 DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
 
@@ -250,6 +252,19 @@ def dfs_attn_clock_probe(counters: torch.Tensor | None):
     """Diagnostic: accumulate shader-clock cycles / 100 MHz ticks / work-group count of the bf16 attention
     kernel into `counters` (3 x int64 on the device, zeroed by the caller); None switches it off."""
     _check(_lib.dfs_attn_clock_probe(_ptr(counters, torch.int64, 3, "counters")))
+
+
+def dfs_probe_mfma(work_groups: int, iters: int, sink: torch.Tensor, counters: torch.Tensor | None = None):
+    """Measurement probe: bare matrix-instruction chains (work_groups x 4 waves x iters x 4 instructions)."""
+    _check(_lib.dfs_probe_mfma(int(work_groups), int(iters), _ptr(sink, torch.float32, work_groups * 256, "sink"),
+                               _ptr(counters, torch.int64, 2, "counters"), _stream()))
+
+
+def dfs_probe_copy(src: torch.Tensor, dst: torch.Tensor):
+    """Measurement probe: plain device copy, 16 bytes per lane."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(_lib.dfs_probe_copy(_ptr(src), _ptr(dst), n, _stream()))
 
 
 def dfs_unperm(g: Geom, dtype: int, o_perm, inv, o):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdfsattn.so")
-SOURCES = ["api.hip", "hilbert.hip", "permute.hip", "score.hip", "select.hip", "attn.hip", "recall.hip"]
+SOURCES = ["api.hip", "hilbert.hip", "permute.hip", "score.hip", "select.hip", "attn.hip", "recall.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

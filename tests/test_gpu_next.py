@@ -136,3 +136,22 @@ def test_attention_clock_probe_counts_every_work_group():
     o_again, _ = G.gpu_attn(g, dt, qp, kp, vp, st)
     torch.cuda.synchronize()
     assert int(probe.cpu()[2]) == groups          # switched off again
+
+
+def test_measurement_probes_run_and_report_sane_rates():
+    """The two probes behind `bench.py --probe`: a short matrix-instruction chain and a copy."""
+    sink = torch.empty(64 * 256, dtype=torch.float32, device="cuda")
+    counters = torch.zeros(2, dtype=torch.int64, device="cuda")
+    P.dfs_probe_mfma(64, 2000, sink, counters)
+    torch.cuda.synchronize()
+    cycles, ticks = (int(x) for x in counters.cpu())
+    assert torch.isfinite(sink).all()
+    assert ticks > 0 and 300.0 < cycles / ticks * 100.0 < 3000.0            # a plausible shader clock in MHz
+    assert 28.0 < cycles / (2000 * 4) < 80.0                                 # about 32 cycles per matrix instruction
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    P.dfs_probe_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(P.DfsError):
+        P.dfs_probe_mfma(0, 10, sink, None)
