@@ -108,7 +108,7 @@ int32_t dfs_keep_count(double sparsity, int32_t M_v);
  *   perm_pad  [N_pad] out  source token of each reordered position, -1 on pad positions
  *   inv       [N]     out  reordered position of each source token
  *   blk_valid [M]     out  real tokens per block (pads are always at a block's tail)
- * Computed once per geometry ("static index mapping", Sec. 6.3).  ws: DFS_WS_HILBERT_PERM.
+ * Computed once per geometry: the map depends on the grid alone (Sec. 6.3).  ws: DFS_WS_HILBERT_PERM.
  */
 int dfs_hilbert_perm(const dfs_geom* g, int32_t* perm_pad, int32_t* inv, int32_t* blk_valid,
                      void* ws, size_t ws_bytes, void* stream);
@@ -175,9 +175,13 @@ int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double spar
  * block and its kv_idx row is not read; with kv_cnt == 0 its output rows are zero.
  * bf16: products on the matrix cores, fp32 accumulation and softmax, output rounded to bf16.
  * f32:  fp32 throughout.
- *   q_perm, k_perm, v_perm [heads, N_pad, d] in;  o_perm [heads, N_pad, d] out (pad rows unspecified)
- *   lse [heads, N_pad] out or NULL: natural-log sum of exp(scale*logit) over the kept keys (the bf16
- *       kernel sums the probabilities as rounded to bf16, the weights O is formed with: 2^-9 relative)
+ *   q_perm, k_perm, v_perm [heads, N_pad, d] in;  o_perm [heads, N_pad, d] out (pad rows unspecified).
+ *       Pad rows of k_perm may hold anything (their logits are discarded); pad rows of v_perm must be
+ *       finite, e.g. the zeros dfs_permute writes: the bf16 kernel multiplies them by a zero weight.
+ *   lse [heads, N_pad] out or NULL: natural-log sum of exp(scale*logit) over the kept keys, fp32-accurate.
+ *       (O is normalised by the sum of the weights as rounded to bf16, the weights its numerator uses; when
+ *       lse is requested the bf16 kernel keeps the unrounded fp32 sum beside it, at a few per cent of its
+ *       speed, because ln of the rounded sum would be off by up to bf16's unit roundoff 2^-8.)
  *   scale: softmax scale, 1/sqrt(d) in the paper.
  */
 int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
@@ -258,8 +262,9 @@ int dfs_schedule(int32_t total_steps, int32_t t, int32_t delta, double cached_ke
  * the caller) is set, every work-group of the bf16 attention kernel adds to counters[0] the shader-clock
  * cycles and to counters[1] the constant-rate timer ticks (100 MHz) between its start and its end, and 1 to
  * counters[2].  counters[0] / counters[1] x 100 MHz is the shader clock the kernel ran at, which on this chip
- * sits well below the nominal 2.4 GHz under matrix load.  NULL switches it off (the default).  Process-wide
- * state, not thread-safe; the buffer must stay valid while set.
+ * sits well below the nominal 2.4 GHz under matrix load.  NULL switches it off (the default).  This is
+ * process-wide state that EVERY later launch of the bf16 attention kernel reads, from any thread and on any
+ * stream: not thread-safe; the buffer (8-byte aligned) must stay valid until it is switched off again.
  */
 int dfs_attn_clock_probe(uint64_t* counters);
 

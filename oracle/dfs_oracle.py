@@ -35,7 +35,7 @@ def cube_bits(T: int, H: int, W: int) -> int:
 def hilbert_key_nd(coords, b: int):
     """Hilbert index of cells in the cube [0,2^b)^n, n = len(coords) (Sec. 5.1 for n = 3).
 
-    The paper names "a 3D Hilbert space-filling curve" without fixing which.  The reading:
+    The paper asks for a 3D Hilbert curve without fixing which of them.  The reading:
     Skilling's transpose form of the Butz curve with the first coordinate the most significant.
     Working from the coarsest bit downward the coordinates are un-rotated (A), then Gray-decoded
     (B), and the n b-bit words are read as b digits of n bits with x0 the high bit of each (C).
@@ -335,7 +335,7 @@ def select_mass_row(score: np.ndarray, mass: float, cap_sparsity: float, M_x: in
 
 def mask_to_lists(mask: np.ndarray, K_max: int):
     """kv_idx [heads, M, K_max] (ascending kept columns, -1 beyond the count) and kv_cnt.
-    A row that keeps all M blocks needs no list; it is listed only if K_max has room for it."""
+    K_max must hold the longest row."""
     heads, M, _ = mask.shape
     kv_idx = np.full((heads, M, K_max), -1, dtype=np.int32)
     kv_cnt = np.zeros((heads, M), dtype=np.int32)
@@ -343,10 +343,7 @@ def mask_to_lists(mask: np.ndarray, K_max: int):
         for u in range(M):
             cols = np.nonzero(mask[h, u])[0]
             kv_cnt[h, u] = cols.shape[0]
-            if cols.shape[0] <= K_max:
-                kv_idx[h, u, :cols.shape[0]] = cols
-            else:
-                assert cols.shape[0] == M
+            kv_idx[h, u, :cols.shape[0]] = cols
     return kv_idx, kv_cnt
 
 

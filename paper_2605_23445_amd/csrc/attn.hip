@@ -68,7 +68,11 @@ __device__ __forceinline__ float max2(float a, float b) {
 // 43 % of the cycles against 57 % for two waves: a wave issues in order, about one instruction per five
 // cycles, and one wave's stream of ~9 instructions per matrix instruction cannot fill the pipe alone.
 // Net 960 against 1070 TFLOP/s on cache-resident keys, so QT = 1 is what is launched.
-template <int D, int BM, int QT>
+//
+// XLSE: the caller wants the log-sum-exp.  The normaliser of O sums the probabilities as rounded to bf16
+// (see `pack` below), which is right for O but leaves ln(sum) off by up to bf16's unit roundoff 2^-8; with
+// XLSE a second running sum of the unrounded fp32 probabilities is kept for the log-sum-exp alone.
+template <int D, int BM, int QT, bool XLSE>
 __global__ void __launch_bounds__(BM * 2 / QT) __attribute__((amdgpu_waves_per_eu(2 / QT, 2 / QT)))
 attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const int32_t* __restrict__ kv_idx, const int32_t* __restrict__ kv_cnt, int K_max, uint16_t* __restrict__ o,
@@ -168,13 +172,13 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) oacc[a][dt][i] = 0.f;
-  float m_run[QT], l_run[QT];
+  float m_run[QT], l_run[QT], x_run[QT];           // x_run: unrounded normaliser (XLSE only)
   // m_run is the reference maximum in the base-2 exponent's units (logit x c2).  It starts at a large
   // finite negative value instead of -inf, so that a row that has only met pad keys (all logits -inf)
   // needs no special case: its differences stay finite and its probabilities are exp2(-inf) = 0.
   constexpr float M_START = -1.0e30f;
 #pragma unroll
-  for (int a = 0; a < QT; ++a) { m_run[a] = M_START; l_run[a] = 0.f; }
+  for (int a = 0; a < QT; ++a) { m_run[a] = M_START; l_run[a] = 0.f; x_run[a] = 0.f; }
   const float c2 = scale * 1.4426950408889634f;     // softmax in base 2
 
   // Tile loads, global memory straight into LDS: instruction j of this wave fills the 64 consecutive
@@ -214,7 +218,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
       const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(sj)), hi = __builtin_amdgcn_readfirstlane(uint32_t(sj >> 32));
       const uint64_t sbase = (uint64_t(hi) << 32) | lo;
       const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + uint32_t(j * NW * 1024));
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
     }
   };
 
@@ -290,7 +294,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         frag[f] = k_frag(tK, f / 2);
       }
     };
-    float mx_a = 0.f, mx_b = 0.f, mx_c = 0.f, mx_d = 0.f, mx = 0.f, mc = 0.f, psum = 0.f;
+    float mx_a = 0.f, mx_b = 0.f, mx_c = 0.f, mx_d = 0.f, mx = 0.f, mc = 0.f, psum = 0.f, xsum = 0.f;
     bool move = false;
     float pe[16];
     // Rounds a pair of probabilities to bf16 and adds them, as rounded, to the normaliser: numerator and
@@ -299,6 +303,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     auto pack = [&](int a, int i) {
       const bf16x2 pk = {(__bf16)pe[i], (__bf16)pe[i + 1]};
       psum = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, psum, false);
+      if (XLSE) xsum += pe[i] + pe[i + 1];
       pc[a][i / 8][(i % 8) / 2] = __builtin_bit_cast(uint32_t, pk);
     };
     if (DO_S) {
@@ -334,6 +339,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
           mx_c = max3(x[6], x[7], x[8]);
           mx_d = max3(x[9], x[10], x[11]);
           psum = 0.f;
+          xsum = 0.f;
         } else if (ph == 1) {
           mx_a = max3(mx_a, mx_b, mx_c);
           mx_d = max3(mx_d, x[12], x[13]);
@@ -369,6 +375,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
           moved[a] = __builtin_amdgcn_ballot_w64(move) != 0;
           m_run[a] = mc;
           l_run[a] = l_run[a] * alpha[a] + psum;
+          if (XLSE) x_run[a] = x_run[a] * alpha[a] + xsum;
           asm volatile("" : "+v"(l_run[a]), "+v"(alpha[a]));
         }
       }
@@ -476,9 +483,12 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
           *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * j + 4 * h) = __builtin_bit_cast(u32x2, w);
         }
     }
-    if (lse && h == 0)
-      lse[int64_t(head) * N_pad + q_row0 + 32 * a] =
-          l_tot > 0.f ? (m_run[a] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+    if (XLSE) {
+      const float x_tot = x_run[a] + __shfl_xor(x_run[a], 32, 64);
+      if (lse && h == 0)
+        lse[int64_t(head) * N_pad + q_row0 + 32 * a] =
+            x_tot > 0.f ? (m_run[a] + __builtin_amdgcn_logf(x_tot)) * 0.6931471805599453f : -INFINITY;
+    }
   }
 }
 
@@ -578,14 +588,16 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
     const int mapping = chunk >= 64 ? 2 : 1;
     const int per_xcd = mapping == 2 ? (g->heads * s.M_x + 7) / 8 + g->heads * chunk : int((total + 7) / 8);
     dim3 grid(unsigned(per_xcd * 8));
-#define ATTN(DD, BB, QQ)                                                                                                    \
-  attn_bf16_kernel<DD, BB, QQ><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
-                                                             static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
-                                                             static_cast<uint16_t*>(o), lse, row_index, s.N, s.N_pad, s.N_v,  \
-                                                             g->n_text, s.M_v, s.M, int(total), per_xcd, mapping, scale, g_clock_probe)
+#define ATTN_X(DD, BB, QQ, XX)                                                                                                  \
+  attn_bf16_kernel<DD, BB, QQ, XX><<<grid, BB * 2 / QQ, 0, st>>>(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), \
+                                                                 static_cast<const uint16_t*>(v), kv_idx, kv_cnt, K_max,          \
+                                                                 static_cast<uint16_t*>(o), lse, row_index, s.N, s.N_pad, s.N_v,  \
+                                                                 g->n_text, s.M_v, s.M, int(total), per_xcd, mapping, scale, g_clock_probe)
+#define ATTN(DD, BB, QQ) do { if (lse) ATTN_X(DD, BB, QQ, true); else ATTN_X(DD, BB, QQ, false); } while (0)
     if (g->d == 64) { if (g->B == 64) ATTN(64, 64, 1); else ATTN(64, 128, 1); }
     else            { if (g->B == 64) ATTN(128, 64, 1); else ATTN(128, 128, 1); }
 #undef ATTN
+#undef ATTN_X
   } else {
     if (row_index) return fail(DFS_EDTYPE, "dfs_sparse_attn_fwd: reading Q / writing O through the permutation needs bf16 tensors");
     if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
@@ -607,6 +619,7 @@ int run_sparse_attn(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
 using namespace dfs;
 
 extern "C" int dfs_attn_clock_probe(uint64_t* counters) {
+  if (misaligned(8, {counters})) return fail(DFS_EINVAL, "dfs_attn_clock_probe: counters must be 8-byte aligned");
   g_clock_probe = reinterpret_cast<unsigned long long*>(counters);
   return DFS_OK;
 }

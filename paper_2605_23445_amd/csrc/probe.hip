@@ -46,6 +46,7 @@ using namespace dfs;
 extern "C" int dfs_probe_mfma(int32_t work_groups, int32_t iters, float* sink, uint64_t* counters, void* stream) {
   if (work_groups < 1 || work_groups > 65535 || iters < 1) return fail(DFS_EINVAL, "dfs_probe_mfma: need 1 <= work_groups <= 65535 and iters >= 1");
   if (!sink) return fail(DFS_EINVAL, "dfs_probe_mfma: NULL sink");
+  if (misaligned(4, {sink}) || misaligned(8, {counters})) return fail(DFS_EINVAL, "dfs_probe_mfma: sink must be 4-byte, counters 8-byte aligned");
   mfma_chain_kernel<<<unsigned(work_groups), 256, 0, as_stream(stream)>>>(sink, reinterpret_cast<unsigned long long*>(counters), iters);
   return launch_status("dfs_probe_mfma");
 }

@@ -41,6 +41,8 @@ extern "C" int dfs_recall(const dfs_geom* g, const float* lse_sparse, const floa
   int rc = check_geom(g, &s);
   if (rc) return rc;
   if (!lse_sparse || !lse_dense || !recall) return fail(DFS_EINVAL, "dfs_recall: NULL argument");
+  if (misaligned(4, {lse_sparse, lse_dense, recall})) return fail(DFS_EINVAL, "dfs_recall: fp32 arrays must be 4-byte aligned");
+  if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
   recall_kernel<<<dim3(unsigned(g->heads)), 256, 0, as_stream(stream)>>>(lse_sparse, lse_dense, recall, s.N_pad, s.N_v,
                                                                         int64_t(s.M_v) * g->B, g->n_text);
   return launch_status("dfs_recall");

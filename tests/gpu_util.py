@@ -74,6 +74,21 @@ def gpu_select(g, score, mode, sparsity, mass=0.0, K_max=None, want_mask=True):
     return P.MaskState(kv_idx, kv_cnt, mask, k_head, K_max)
 
 
+def lists_of_mask(mask_np: np.ndarray, K_max: int):
+    """(kv_idx, kv_cnt) in the library's list format for a 0/1 mask [heads, M, M]: ascending kept columns, -1
+    beyond the count.  The library's convention, not the method's: a row that keeps all M blocks carries no
+    list (kv_cnt == M means dense), so K_max need not hold it."""
+    heads, M, _ = mask_np.shape
+    kv_idx = np.full((heads, M, K_max), -1, dtype=np.int32)
+    kv_cnt = mask_np.sum(axis=2).astype(np.int32)
+    for h in range(heads):
+        for u in range(M):
+            if kv_cnt[h, u] < M or M <= K_max:
+                cols = np.nonzero(mask_np[h, u])[0]
+                kv_idx[h, u, :cols.size] = cols
+    return kv_idx, kv_cnt
+
+
 def upload_mask(mask_np: np.ndarray, K_max=None) -> P.MaskState:
     """Device kv lists built on the host from a 0/1 mask [heads, M, M] (rows that keep all M blocks get
     no list, like the library's own)."""

@@ -59,7 +59,9 @@ def test_recall_against_the_definition():
         got = recall.cpu().numpy()
         want = O.attention_recall(G.as_f64_dev(qp), G.as_f64_dev(kp), st.mask.cpu().numpy(), blk_valid, w.B)
         print(f"  sparsity {sp}: recall {got} oracle {want}", flush=True)
-        assert np.abs(got - want).max() <= 5e-3                  # lse of the bf16 kernel is good to 2^-9 relative
+        # recall = mean of exp(lse_sparse - lse_dense) <= 1: an lse good to 1e-4 (the parity bound) moves it by
+        # at most 2e-4; the mean over the rows is taken in fp32
+        assert np.abs(got - want).max() <= 2e-4
         assert np.all(got > 1.0 - sp)                            # kept blocks hold more than their share
         if prev is not None:
             assert np.all(got <= prev + 1e-3)                    # fewer kept blocks, less mass

@@ -203,6 +203,35 @@ def test_mass_rule_brute_force_mean():
             assert list(np.nonzero(mask[h, u])[0]) == _brute_topk_row(score[h, u], int(k_head[h]))
 
 
+def test_mass_rule_equals_the_plain_cumulative_definition_exactly():
+    """On rows whose scores are multiples of 2^-10 (so that fixed point loses nothing) the keep count is the plain
+    definition - the fewest top-ranked blocks whose scores sum to at least mass x the row total - evaluated in
+    exact rational arithmetic.  Rows where some prefix sum sits within two fixed-point units of the target are
+    left out (none for the dyadic mass, where the target itself is exact)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(17)
+    M_v = 48
+    checked = 0
+    for trial in range(300):
+        ints = rng.choice(1 << 14, size=M_v, replace=False)               # distinct, so the ranking has no ties
+        row = (ints.astype(np.float64) / 1024.0).astype(np.float32)       # exact in fp32: 14 significant bits
+        exact = sorted((Fraction(int(i), 1024) for i in ints), reverse=True)
+        total = sum(exact)
+        for mass in (0.75, 0.5, 0.9, 0.33):
+            target = Fraction(mass) * total                                # Fraction(float) is exact
+            run, k_def, near = Fraction(0), None, False
+            for k, x in enumerate(exact, start=1):
+                run += x
+                near |= abs(run - target) * (1 << 24) < 2
+                if k_def is None and run >= target:
+                    k_def = k
+            if near and mass not in (0.75, 0.5):
+                continue
+            assert O.mass_keep_count(row, mass) == k_def, (trial, mass)
+            checked += 1
+    assert checked >= 1150
+
+
 def test_mass_row_rule():
     M_v = 40
     score = np.zeros((1, M_v, M_v), dtype=np.float32)
