@@ -168,6 +168,21 @@ int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double spar
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * dfs_select_mask for callers that can neither allocate nor pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), same results bit for bit.
+ * The scratch of the mass modes (the per-row and per-head keep counts, 4 (heads M_v + heads) bytes) lives in a
+ * 1 MiB buffer inside the library, one per GPU, held until the process ends; a geometry that needs more
+ * (heads x M_v above about 260 000) is refused with DFS_EWORKSPACE before anything is launched.  The call
+ * allocates and frees nothing.  The first call on a device looks up the buffer's device address (no
+ * allocation; make that call outside a graph capture).  Every call on a GPU uses that GPU's one buffer, which
+ * keeps the last call's contents; nothing in it has to start at zero (every word is written before it is
+ * read), but two calls that overlap in time on one GPU, e.g. on two streams, race on it.
+ */
+int dfs_select_mask_static(const dfs_geom* g, const float* score, int mode, double sparsity, double mass,
+                           uint8_t* mask, int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max, int32_t* k_head,
+                           void* stream);
+
+/*
  * Block-sparse attention forward over the reordered sequence (Algorithm 1 step 3; Eq. 1 on the
  * kept block pairs).  For a real query position p in block u, the keys are the real positions of
  * the blocks kv_idx[h,u,0..kv_cnt[h,u]) and o_perm[h,p,:] = sum_j softmax_j(scale <q_p,k_j>) v_j

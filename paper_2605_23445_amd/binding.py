@@ -70,6 +70,7 @@ def _load():
         "dfs_permute": (C.c_int, [gp, C.c_int, vp, vp, vp, vp]),
         "dfs_block_score": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, sz, vp]),
         "dfs_select_mask": (C.c_int, [gp, vp, C.c_int, dbl, dbl, vp, vp, vp, i32, vp, vp, sz, vp]),
+        "dfs_select_mask_static": (C.c_int, [gp, vp, C.c_int, dbl, dbl, vp, vp, vp, i32, vp, vp]),
         "dfs_sparse_attn_fwd": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]),
         "dfs_unperm": (C.c_int, [gp, C.c_int, vp, vp, vp, vp]),
         "dfs_block_score_src": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, sz, vp]),
@@ -90,7 +91,8 @@ def _load():
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
            "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
-           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused", "dfs_probe_mfma", "dfs_probe_copy")
+           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused", "dfs_probe_mfma", "dfs_probe_copy",
+           "dfs_select_mask_static")
 DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
 
@@ -201,6 +203,15 @@ def dfs_select_mask(g: Geom, score, mode: int, sparsity: float, mass: float, mas
                                 _ptr(kv_idx, torch.int32, g.heads * s.M * K_max, "kv_idx"),
                                 _ptr(kv_cnt, torch.int32, g.heads * s.M, "kv_cnt"), int(K_max),
                                 _ptr(k_head, torch.int32, g.heads, "k_head"), wp, wb, _stream()))
+
+
+def dfs_select_mask_static(g: Geom, score, mode: int, sparsity: float, mass: float, mask, kv_idx, kv_cnt, K_max: int, k_head):
+    s = dfs_geom_sizes(g)
+    _check(_lib.dfs_select_mask_static(C.byref(g), _ptr(score, torch.float32, g.heads * s.M_v * s.M_v, "score"), mode,
+                                       float(sparsity), float(mass), _ptr(mask, torch.uint8, g.heads * s.M * s.M, "mask"),
+                                       _ptr(kv_idx, torch.int32, g.heads * s.M * K_max, "kv_idx"),
+                                       _ptr(kv_cnt, torch.int32, g.heads * s.M, "kv_cnt"), int(K_max),
+                                       _ptr(k_head, torch.int32, g.heads, "k_head"), _stream()))
 
 
 def dfs_sparse_attn_fwd(g: Geom, dtype: int, q_perm, k_perm, v_perm, kv_idx, kv_cnt, K_max: int, scale: float,

@@ -8,9 +8,17 @@
 // "higher score first, equal scores by lower index".
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace dfs {
+
+// Scratch of dfs_select_mask_static: the per-row and per-head keep counts of the mass modes live here instead
+// of in a caller-supplied workspace.  One copy per GPU, held until the process ends.  Host code never uses the
+// symbol's name as an address: the device address is resolved once per device (static_scratch below).
+constexpr size_t STATIC_SCRATCH_BYTES = size_t(1) << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 constexpr int MASS_FRAC_BITS = 24;
 
@@ -204,9 +212,45 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
   return launch_status("dfs_select_mask");
 }
 
+// Device address of `scratch` on the current device, resolved on the first call per device and kept.
+static int static_scratch(void** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* addr[MAX_DEV] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(DFS_EHIP, "dfs_select_mask_static: hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= MAX_DEV) return fail(DFS_EHIP, "dfs_select_mask_static: device ordinal %d is outside [0,%d)", dev, MAX_DEV);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(DFS_EHIP, "dfs_select_mask_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    addr[dev] = p;
+  }
+  *out = addr[dev];
+  return DFS_OK;
+}
+
 }  // namespace dfs
 
 using namespace dfs;
+
+extern "C" int dfs_select_mask_static(const dfs_geom* g, const float* score, int mode, double sparsity, double mass, uint8_t* mask,
+                                      int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max, int32_t* k_head, void* stream) {
+  dfs_sizes s;
+  int rc = check_geom(g, &s);
+  if (rc) return rc;
+  if (!score || !kv_idx || !kv_cnt) return fail(DFS_EINVAL, "dfs_select_mask_static: NULL argument");
+  if (misaligned(4, {score, kv_idx, kv_cnt, k_head})) return fail(DFS_EINVAL, "dfs_select_mask_static: score, list and count arrays must be 4-byte aligned");
+  const size_t need = ws_select_mask(g, s);
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(DFS_EWORKSPACE, "dfs_select_mask_static: heads x M_v = %d x %d needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                                "use dfs_select_mask with a workspace", g->heads, s.M_v, need, STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  return run_select_mask(g, s, score, mode, sparsity, mass, mask, kv_idx, kv_cnt, K_max, k_head, ws, as_stream(stream));
+}
 
 extern "C" int dfs_select_mask(const dfs_geom* g, const float* score, int mode, double sparsity, double mass, uint8_t* mask,
                                int32_t* kv_idx, int32_t* kv_cnt, int32_t K_max, int32_t* k_head, void* ws, size_t ws_bytes,
