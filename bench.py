@@ -10,6 +10,11 @@ region.  Prints ONE JSON line.
 
 --workload wan_cache runs the mask-caching schedule instead (Q, K drift per step, masks from the adaptive
 per-head ratio every few steps, reused in between) and reports refresh-step and reuse-step times.
+--workload wan_paper_schedule walks the paper's own 50-step schedule (Sec. 6.1, App. B: first quarter of the
+steps dense, then keep 0.3 / 0.2 / 0.1, mask refreshed every 12 steps) on the wan shape and reports the attention
+time of a whole sampling run against 50 dense steps (a kernel-level figure to set beside the paper's Table 2).
+--ablation prints, for the four token orders of Table 3 x the sub-block sizes of Table 4, the attention recall
+(Eq. 3) of the selected mask and the cost of the scoring stage, on a few heads of the workload.
 """
 from __future__ import annotations
 
@@ -26,9 +31,34 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
-# HBM-side traffic of the attention kernel per launch on the default workload (wan, sparsity 0.9), from
-# profiles/wan90_attention_counters.txt: FETCH_SIZE x 2.00 and WRITE_SIZE x 1.00, in bytes.
-RECORDED_TRAFFIC = {("wan", 0.9): (30326000 * 1024 * 2.0, 756902 * 1024 * 1.0)}
+# What this chip sustains (profiles/mi355x_sustained_rates.txt; `--probe` re-measures): bare chains of the
+# matrix instruction the attention kernel uses, and the fastest plain row gather.
+MEASURED_MFMA_TFLOPS = 2141.0
+MEASURED_COPY_GBS = 5830.0
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "wan90_attention_counters.txt")
+ATTN_SOURCE = os.path.join(ROOT, "paper_2605_23445_amd", "csrc", "attn.hip")
+
+
+def recorded_traffic(workload, sparsity):
+    """HBM-side bytes of the attention kernel per launch as recorded under profiles/ (rocprofv3 --pmc FETCH_SIZE
+    and WRITE_SIZE, already scaled by the copy calibration).  The record names the workload it was taken on and
+    the SHA-256 of the kernel source it was taken with; it is used only if both match what runs now, so a
+    changed kernel reports no traffic instead of a stale one."""
+    import hashlib
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+        digest = hashlib.sha256(open(ATTN_SOURCE, "rb").read()).hexdigest()
+    except OSError:
+        return None, "no traffic record under profiles/"
+    m = re.search(r"^record: workload=(\S+) sparsity=(\S+) attn_source_sha256=(\S+) fetch_bytes=(\S+) write_bytes=(\S+)", text, re.M)
+    if not m:
+        return None, "profiles/wan90_attention_counters.txt holds no record line"
+    if m.group(1) != workload or abs(float(m.group(2)) - sparsity) > 1e-9:
+        return None, f"the record under profiles/ is for {m.group(1)} at sparsity {m.group(2)}"
+    if m.group(3) != digest:
+        return None, "the attention kernel source changed since the record under profiles/ was taken"
+    return (float(m.group(4)), float(m.group(5))), "profiles/wan90_attention_counters.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, scaled by a 1 GiB copy)"
 
 
 def parse():
@@ -48,7 +78,10 @@ def parse():
                     help="also run one plain 1 GiB device copy before the warm-up (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
                     help="scaled rocprofv3 FETCH_SIZE / WRITE_SIZE of the attention kernel, KiB per launch "
-                         "(default: the values recorded in profiles/ for the default workload)")
+                         "(default: the record under profiles/, if it was taken on this workload with this kernel source)")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark: recall (Eq. 3) and scoring-stage time for the token orders of Table 3 x the "
+                         "sub-block sizes of Table 4 (one JSON line)")
     return ap.parse_args()
 
 
@@ -65,6 +98,10 @@ def main():
     from workloads import CONFIGS, derived_sizes, make_qkv
     if a.probe:
         return probe_rates(P, torch)
+    if a.workload == "wan_paper_schedule":
+        return paper_schedule_bench(a, P)
+    if a.ablation:
+        return ablation(a, P)
 
     w = CONFIGS[a.workload]
     if a.heads:
@@ -149,8 +186,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_step = wall * 1e3 / a.steps
-    stage_ms = {name: sum(events[s * 7 + i].elapsed_time(events[s * 7 + i + 1]) for s in range(a.steps)) / a.steps
-                for i, name in enumerate(stages)}
+    per_step = {name: [events[s * 7 + i].elapsed_time(events[s * 7 + i + 1]) for s in range(a.steps)] for i, name in enumerate(stages)}
+    stage_ms = {name: float(np.mean(v)) for name, v in per_step.items()}
+    stage_stats = {name: {"mean": round(float(np.mean(v)), 4), "median": round(float(np.median(v)), 4), "min": round(float(np.min(v)), 4)}
+                   for name, v in per_step.items()}
 
     # Shader clock under the attention kernel, from two extra untimed steps with the kernel's own clock probe
     # (cycle counter against the constant-rate 100 MHz counter): the chip runs well below its nominal 2.4 GHz
@@ -175,13 +214,24 @@ def main():
     bytes_permute = n_perm * w.heads * (sz["N"] + N_pad) * w.d * e + n_perm * N_pad * 4
     bytes_unperm = 2 * w.heads * sz["N"] * w.d * e + sz["N"] * 4
     if a.traffic_kib is not None:
-        rec = (a.traffic_kib[0] * 1024, a.traffic_kib[1] * 1024)
+        rec, rec_src = (a.traffic_kib[0] * 1024, a.traffic_kib[1] * 1024), "--traffic-kib"
+    elif a.heads:
+        rec, rec_src = None, "head count overridden"
     else:
-        rec = RECORDED_TRAFFIC.get((w.name, a.sparsity)) if not a.heads else None
+        rec, rec_src = recorded_traffic(w.name, a.sparsity)
     traffic = None if rec is None else rec[0] + rec[1]
-    traffic_detail = None if rec is None else {
-        "fetch_bytes": rec[0], "write_bytes": rec[1], "algorithmic_bytes": 4.0 * w.heads * N_pad * w.d * e,
-        "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, scaled by a 1 GiB copy (profiles/wan90_attention_counters.txt)"}
+    traffic_detail = {"algorithmic_bytes": 4.0 * w.heads * N_pad * w.d * e, "source": rec_src, "measured_in_this_run": False}
+    if rec is not None:
+        traffic_detail.update({"fetch_bytes": rec[0], "write_bytes": rec[1]})
+    # scoring stage against HBM (pooling reads Q and K and, in the fused form, writes K'; the pooled planes, the
+    # per-(query sub-block, key block) log-sums and the scores follow): algorithmic bytes = inputs read once +
+    # scores written once; "moved" adds what the kernels also write and re-read on the way
+    r_sub = w.B // w.Bs
+    M_s = M_v * r_sub
+    score_alg = 2.0 * w.heads * (sz["N"] if fused else N_pad) * w.d * e + w.heads * M_v * M_v * 4.0
+    planes = 2.0 * w.heads * M_s * 3 * w.d * 2
+    score_moved = score_alg + (w.heads * N_pad * w.d * e if fused else 0.0) + 2 * planes + 2.0 * w.heads * M_v * M_s * 4
+    select_bytes = w.heads * M_v * M_v * 4.0 + w.heads * M * (K_max + 1) * 4.0
     out = {
         "metric": "dense-equivalent attention TFLOP/s of one whole DFSAttn step (reorder + block scoring + "
                   "top-k selection + block-sparse attention + inverse reorder) at the given sparsity",
@@ -200,15 +250,228 @@ def main():
         "mfma_util_pct_at_measured_clock": None if not clock_mhz else
             100.0 * flop_exec / (attn_ms * 1e-3) / (256 * 4 * 1024.0 * clock_mhz * 1e6),
         "stage_ms": {k2: round(v2, 4) for k2, v2 in stage_ms.items()},
+        "stage_ms_stats": stage_stats,
         "permute_gbs": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9,
+        "permute_hbm_frac": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "unperm_gbs": None if fused else bytes_unperm / (stage_ms["unperm"] * 1e-3) / 1e9,
+        "unperm_note": "O is written in source order by the attention kernel; no separate pass runs" if fused else None,
+        "score_gbs": score_alg / (stage_ms["block_score"] * 1e-3) / 1e9,
+        "score_hbm_frac": score_alg / (stage_ms["block_score"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "score_moved_gbs": score_moved / (stage_ms["block_score"] * 1e-3) / 1e9,
+        "score_note": "block_score = pooling (HBM-bound) + the sub-block logits as six bf16 products per fp32 logit on the matrix "
+                      "cores + fold; the stage is bound by that contraction, not by memory",
+        "select_gbs": select_bytes / (stage_ms["select_mask"] * 1e-3) / 1e9,
+        "score_plus_select_ms": stage_ms["block_score"] + stage_ms["select_mask"],
+        "measured_peaks": {"mfma_chain_tflops": MEASURED_MFMA_TFLOPS, "row_gather_gbs": MEASURED_COPY_GBS,
+                           "attn_frac_of_measured_mfma": flop_exec / (attn_ms * 1e-3) / 1e12 / MEASURED_MFMA_TFLOPS,
+                           "permute_frac_of_measured_copy": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9 / MEASURED_COPY_GBS,
+                           "source": "profiles/mi355x_sustained_rates.txt (bench.py --probe)"},
+        "binding_bound": ("attention: bf16 matrix cores (at d = 64 the vector work per matrix instruction doubles and the "
+                          "kernel is bound by vector issue and power instead); permute: HBM; scoring: its fp32-accurate contraction"),
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
                      "achieved": flop_exec / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_exec / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "launch_ms": {"mean": attn_ms, "median": stage_stats["sparse_attn"]["median"], "min": stage_stats["sparse_attn"]["min"]},
                      "traffic": traffic, "traffic_detail": traffic_detail},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, sz, a.sparsity, q, k, v, flop_dense)
+    print(json.dumps(out))
+
+
+def _inputs(P, w):
+    """Seeded Q, K, V of a workload as device tensors (generation time is reported, not timed)."""
+    import torch
+    from workloads import make_qkv
+    t0 = time.time()
+    q, k, v = make_qkv(w)
+    dev = []
+    for x in (q, k, v):
+        t = torch.from_numpy(x)
+        dev.append((t.view(torch.bfloat16) if w.dtype == "bf16" else t).cuda())
+    return dev, time.time() - t0
+
+
+def paper_schedule_bench(a, P):
+    """One sampling run of one attention layer under the paper's schedule (Sec. 6.1 and App. B: the first quarter of
+    the steps dense, then keep ratios 0.3, 0.2, 0.1 a quarter each; Algorithm 1: the mask is recomputed when t is a
+    multiple of delta = 12, here also when the keep ratio changes), on the wan shape.  Dense steps run the same
+    attention kernel with every block kept.  The token order is computed once (Sec. 6.3).  Q, K, V stay fixed over
+    the steps: the cost of a step depends on the schedule, not on the values."""
+    import numpy as np
+    import torch
+    from workloads import CONFIGS, derived_sizes
+    w = CONFIGS["wan"]
+    if a.heads:
+        w = w.with_heads(a.heads)
+    total_steps = a.steps if a.steps else 50
+    delta = 12
+    sz = derived_sizes(w)
+    torch.cuda.set_device(0)
+    g = P.Geom(w.T, w.H, w.W, w.n_text, w.heads, w.d, w.B, w.Bs)
+    dt = P.DFS_BF16
+    (qd, kd, vd), gen_s = _inputs(P, w)
+    N_pad, M, M_v, M_x = sz["N_pad"], sz["M"], sz["M_v"], sz["M_x"]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    perm_pad, inv, blk_valid = torch.empty(N_pad, **i32), torch.empty(sz["N"], **i32), torch.empty(M, **i32)
+    kp, vp = (torch.empty((w.heads, N_pad, w.d), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    o = torch.empty_like(qd)
+    score = torch.empty((w.heads, M_v, M_v), dtype=torch.float32, device="cuda")
+    K_max = P.dfs_keep_count(0.7, M_v) + M_x
+    kv_idx, kv_cnt = torch.empty((w.heads, M, K_max), **i32), torch.empty((w.heads, M), **i32)
+    all_cnt = torch.full((w.heads, M), M, **i32)          # every block kept: rows carry no list
+    ws = torch.empty(max(P.dfs_workspace_bytes(g, kk) for kk in (P.DFS_WS_HILBERT_PERM, P.DFS_WS_BLOCK_SCORE, P.DFS_WS_SELECT_MASK)),
+                     dtype=torch.uint8, device="cuda")
+    scale = 1.0 / math.sqrt(w.d)
+    P.dfs_hilbert_perm(g, perm_pad, inv, blk_valid, ws)
+
+    def one(dense, refresh, sparsity, ev):
+        ev[0].record()
+        if dense:
+            P.dfs_permute(g, dt, kd, perm_pad, kp)
+            P.dfs_permute(g, dt, vd, perm_pad, vp)
+            ev[1].record()
+            P.dfs_sparse_attn_fwd_src(g, dt, qd, perm_pad, kp, vp, kv_idx, all_cnt, K_max, scale, o, None)
+        else:
+            if refresh:
+                P.dfs_permute(g, dt, vd, perm_pad, vp)
+                P.dfs_block_score_fused(g, dt, qd, kd, perm_pad, kp, score, ws)
+                P.dfs_select_mask(g, score, P.DFS_SELECT_TOPK, sparsity, 0.0, None, kv_idx, kv_cnt, K_max, None, ws)
+            else:
+                P.dfs_permute(g, dt, kd, perm_pad, kp)
+                P.dfs_permute(g, dt, vd, perm_pad, vp)
+            ev[1].record()
+            P.dfs_sparse_attn_fwd_src(g, dt, qd, perm_pad, kp, vp, kv_idx, kv_cnt, K_max, scale, o, None)
+        ev[2].record()
+
+    spare = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(max(1, a.warmup // 2)):
+        one(True, False, 0.0, spare)
+        one(False, True, 0.8, spare)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(total_steps)]
+    plan, cached_keep = [], None
+    t_start = time.perf_counter()
+    for t in range(total_steps):
+        dense, refresh, sparsity = P.dfs_schedule(total_steps, t, delta, cached_keep)
+        if not dense and refresh:
+            cached_keep = 1.0 - sparsity
+        plan.append((dense, refresh, sparsity))
+        one(dense, refresh, sparsity, ev[t])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    step_ms = [e[0].elapsed_time(e[2]) for e in ev]
+    attn_ms = [e[1].elapsed_time(e[2]) for e in ev]
+    dense_ms = [step_ms[t] for t in range(total_steps) if plan[t][0]]
+    phases = {}
+    for t, (dense, refresh, sparsity) in enumerate(plan):
+        key = "dense" if dense else f"sparsity {sparsity:.1f}"
+        ph = phases.setdefault(key, {"steps": 0, "refresh_steps": 0, "ms": 0.0, "attn_ms": 0.0})
+        ph["steps"] += 1
+        ph["refresh_steps"] += int(refresh and not dense)
+        ph["ms"] += step_ms[t]
+        ph["attn_ms"] += attn_ms[t]
+    for ph in phases.values():
+        ph["ms_per_step"] = ph["ms"] / ph["steps"]
+    run_ms = float(np.sum(step_ms))
+    dense_run_ms = float(np.mean(dense_ms)) * total_steps if dense_ms else None
+    sparse_steps = [pl[2] for pl in plan if not pl[0]]
+    flop_dense = 4.0 * float(sz["N"]) ** 2 * w.d * w.heads
+    layers = 40          # transformer blocks of the 14B model the shape is taken from; the first one stays dense (App. B)
+    speedup = dense_run_ms / run_ms if dense_run_ms else None
+    out = {
+        "metric": "dense-equivalent attention TFLOP/s of one attention layer over a whole sampling run under the paper's step "
+                  "schedule (first quarter dense, then keep 0.3 / 0.2 / 0.1, mask refreshed every 12 steps)",
+        "value": flop_dense * total_steps / (run_ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": total_steps, "warmup": a.warmup, "ms_per_step": run_ms / total_steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"wan_paper_schedule: grid {w.T}x{w.H}x{w.W}, {sz['N']} tokens, {w.heads} heads, d={w.d}, B={w.B}, Bs={w.Bs}; "
+                               f"{total_steps} steps, delta {delta}", "input_gen_s": round(gen_s, 1)},
+        "run_ms": run_ms, "wall_ms": wall_ms, "dense_run_ms": dense_run_ms,
+        "mean_sparsity_of_sparse_steps": float(np.mean(sparse_steps)) if sparse_steps else None,
+        "phases": phases,
+        "attention_speedup_over_dense_run": speedup,
+        "model_level_attention_speedup_first_block_dense": None if speedup is None else
+            layers * dense_run_ms / (dense_run_ms + (layers - 1) * run_ms),
+        "paper_context": "Table 2 reports 1.79x end to end for Wan2.1-14B (dense FlashAttention-2 baseline, H100, its own third-party "
+                         "sparse kernel, 78.5 % mean sparsity); that figure includes everything outside attention, this one is "
+                         "attention alone on MI355X",
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": None, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": None, "traffic": None},
+    }
+    pairs_dense = float(w.heads) * M * M
+    if dense_ms:
+        d_attn = float(np.mean([attn_ms[t] for t in range(total_steps) if plan[t][0]]))
+        out["roofline"]["achieved"] = pairs_dense * 4.0 * w.B * w.B * w.d / (d_attn * 1e-3) / 1e12
+        out["roofline"]["frac"] = out["roofline"]["achieved"] / PEAK_BF16_TFLOPS
+        out["roofline"]["note"] = "dense steps (every block kept)"
+    print(json.dumps(out))
+
+
+def ablation(a, P):
+    """Token orders (Table 3) x sub-block sizes (Table 4): attention recall (Eq. 3) of the mask each combination selects at
+    the given sparsity, and the time of the scoring stage, on a few heads of the workload.  Recall is the quality proxy
+    that needs no model weights: the share of the full attention mass that falls on kept blocks."""
+    import numpy as np
+    import torch
+    from workloads import CONFIGS, derived_sizes
+    w = CONFIGS[a.workload].with_heads(a.heads if a.heads else 4)
+    sparsity = 0.9 if a.sparsity is None else a.sparsity
+    sz = derived_sizes(w)
+    torch.cuda.set_device(0)
+    dt = P.DFS_BF16
+    assert w.dtype == "bf16", "the ablation runs on a bf16 workload"
+    (qd, kd, vd), gen_s = _inputs(P, w)
+    N_pad, M, M_v, M_x = sz["N_pad"], sz["M"], sz["M_v"], sz["M_x"]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    g0 = P.Geom(w.T, w.H, w.W, w.n_text, w.heads, w.d, w.B, w.Bs)
+    perm_pad, inv, blk_valid = torch.empty(N_pad, **i32), torch.empty(sz["N"], **i32), torch.empty(M, **i32)
+    qp, kp, vp, op = (torch.empty((w.heads, N_pad, w.d), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    score = torch.empty((w.heads, M_v, M_v), dtype=torch.float32, device="cuda")
+    k_keep = P.dfs_keep_count(sparsity, M_v)
+    K_max = k_keep + M_x
+    kv_idx, kv_cnt = torch.empty((w.heads, M, K_max), **i32), torch.empty((w.heads, M), **i32)
+    all_cnt = torch.full((w.heads, M), M, **i32)
+    lse_d, lse_s = (torch.empty((w.heads, N_pad), dtype=torch.float32, device="cuda") for _ in range(2))
+    recall = torch.empty(w.heads, dtype=torch.float32, device="cuda")
+    scale = 1.0 / math.sqrt(w.d)
+    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    orders = (("hilbert3d", P.DFS_ORDER_HILBERT3D), ("raster", P.DFS_ORDER_RASTER), ("hilbert2d", P.DFS_ORDER_HILBERT2D),
+              ("block3d", P.DFS_ORDER_BLOCK3D))
+    sub_blocks = [bs for bs in (16, 32, 64, 128) if w.B % bs == 0 and bs <= w.B]
+    table = {}
+    reps = 5
+    for name, order in orders:
+        gs = {bs: P.Geom(w.T, w.H, w.W, w.n_text, w.heads, w.d, w.B, bs) for bs in sub_blocks}
+        ws = torch.empty(max(max(P.dfs_workspace_bytes(gg, kk) for kk in (P.DFS_WS_HILBERT_PERM, P.DFS_WS_BLOCK_SCORE, P.DFS_WS_SELECT_MASK))
+                             for gg in gs.values()), dtype=torch.uint8, device="cuda")
+        P.dfs_token_order(g0, order, perm_pad, inv, blk_valid, ws)
+        for x, xp in ((qd, qp), (kd, kp), (vd, vp)):
+            P.dfs_permute(g0, dt, x, perm_pad, xp)
+        P.dfs_sparse_attn_fwd(g0, dt, qp, kp, vp, kv_idx, all_cnt, K_max, scale, op, lse_d)     # every block kept
+        row = {}
+        for bs, gg in gs.items():
+            P.dfs_block_score(gg, dt, qp, kp, score, ws)                                          # warm-up
+            e0.record()
+            for _ in range(reps):
+                P.dfs_block_score(gg, dt, qp, kp, score, ws)
+            e1.record()
+            for _ in range(reps):
+                P.dfs_select_mask(gg, score, P.DFS_SELECT_TOPK, sparsity, 0.0, None, kv_idx, kv_cnt, K_max, None, ws)
+            e2.record()
+            P.dfs_sparse_attn_fwd(gg, dt, qp, kp, vp, kv_idx, kv_cnt, K_max, scale, op, lse_s)
+            P.dfs_recall(gg, lse_s, lse_d, recall)
+            torch.cuda.synchronize()
+            rc = recall.cpu().numpy()
+            row[f"Bs={bs}"] = {"recall_mean": float(rc.mean()), "recall_min": float(rc.min()),
+                               "block_score_ms": e0.elapsed_time(e1) / reps, "select_mask_ms": e1.elapsed_time(e2) / reps}
+        table[name] = row
+        del ws
+    out = {"ablation": "attention recall (Eq. 3) of the selected mask and scoring-stage time: token orders of Table 3 x sub-block sizes of "
+                       "Table 4 (Bs = B is the variant without sub-blocks)",
+           "config": {"workload": f"{w.name}: grid {w.T}x{w.H}x{w.W} (+{w.n_text} text), {sz['N']} tokens, {w.heads} heads, d={w.d}, B={w.B}",
+                      "sparsity": sparsity, "kept_blocks_per_row": k_keep, "input_gen_s": round(gen_s, 1)},
+           "recall_of_a_random_mask": k_keep / float(M_v), "data": "synthetic", "table": table}
     print(json.dumps(out))
 
 
