@@ -1,8 +1,8 @@
 // Block-mask selection (paper Eq. 9) and the cumulative-mass keep count.
 //
 // One wave owns one (head, query block) row of scores.  Scores are mapped to 32-bit keys whose
-// unsigned order is the float order; the k-th largest key is found by fixing its bits from the top
-// (32 counting passes over the row in LDS), ties at the threshold are resolved towards the lower
+// unsigned order is the float order; the k-th largest key is found a byte at a time from the top (four
+// histogram passes over the row in LDS), ties at the threshold are resolved towards the lower
 // column index, and the kept columns are written in ascending order with ballot prefix sums.
 // Everything is integer work on the bit patterns, so the result is exactly the total order
 // "higher score first, equal scores by lower index".
@@ -141,18 +141,45 @@ __global__ void __launch_bounds__(64) select_kernel(const float* __restrict__ sc
   const float* row = score + (int64_t(head) * M_v + u) * M_v;
   for (int j = lane; j < M_v; j += 64) keys[j] = order_key(row[j]);
   __syncthreads();
-  // T = k-th largest key: the largest T with at least k keys >= T
-  uint32_t T = 0;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t cand = T | (1u << bit);
-    uint32_t c = 0;
-    for (int j = lane; j < M_v; j += 64) c += keys[j] >= cand ? 1u : 0u;
-    if (wave_sum_u32(c) >= uint32_t(k)) T = cand;
+  // T = k-th largest key, found a byte at a time from the top: a 256-bin histogram of the next byte of the keys that
+  // still match the bytes fixed so far, then the bin in which the count from the top reaches what is still wanted.
+  // Four passes instead of one per bit; counts are integers, so the result is the same key.
+  uint32_t* hist = keys + M_v;
+  uint32_t T = 0, fixed = 0, want = uint32_t(k);      // want: rank of the key looked for among the keys matching T on `fixed`
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int b = lane; b < 256; b += 64) hist[b] = 0u;
+    __syncthreads();
+    for (int j = lane; j < M_v; j += 64) {
+      const uint32_t key = keys[j];
+      if ((key & fixed) == T) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // lane l owns bins 255 - 4 l .. 252 - 4 l, so that lane order is descending key order
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = hist[255 - 4 * lane - i];
+    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    const unsigned long long reached = __ballot(incl >= want);     // never empty: at least `want` keys match
+    const int sel = __ffsll(reached) - 1;
+    uint32_t left = want - (incl - mine), digit = 0u;              // meaningful in lane `sel` only
+#pragma unroll
+    for (int i = 3; i >= 0; --i) {                                 // the first bin (from the top) whose running count reaches `left`
+      const uint32_t before = (i > 0 ? c[0] : 0u) + (i > 1 ? c[1] : 0u) + (i > 2 ? c[2] : 0u);
+      if (before < left && left <= before + c[i]) digit = uint32_t(255 - 4 * lane - i) | ((left - before) << 8);
+    }
+    digit = __shfl(digit, sel, 64);
+    T |= (digit & 255u) << shift;
+    want = digit >> 8;
+    fixed |= 255u << shift;
+    __syncthreads();                                               // the histogram is cleared next
   }
-  uint32_t above = 0;
-  for (int j = lane; j < M_v; j += 64) above += keys[j] > T ? 1u : 0u;
-  above = wave_sum_u32(above);
-  const uint32_t ties_wanted = uint32_t(k) - above;  // lowest-index columns equal to T
+  const uint32_t ties_wanted = want;                               // lowest-index columns equal to T; the k - want keys above T are all kept
   int32_t* idx = kv_idx + (int64_t(head) * M + u) * K_max;
   uint32_t ties_seen = 0, written = 0;
   const unsigned long long below_me = (1ull << lane) - 1ull;
@@ -187,14 +214,15 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
     return fail(DFS_EINVAL, "dfs_select_mask: unknown mode %d", mode);
   if (!(sparsity >= 0.0 && sparsity <= 1.0)) return fail(DFS_EINVAL, "dfs_select_mask: sparsity %g is outside [0,1]", sparsity);
   if (g->heads > 65535) return fail(DFS_ESHAPE, "heads=%d exceeds 65535", g->heads);
-  if (s.M_v > 16384) return fail(DFS_ESHAPE, "dfs_select_mask: M_v=%d exceeds 16384 (one score row must fit in 64 KB of LDS)", s.M_v);
+  if (s.M_v > 16128) return fail(DFS_ESHAPE, "dfs_select_mask: M_v=%d exceeds 16128 (one score row and a histogram must fit in 64 KB of LDS)", s.M_v);
   const int k_base = dfs_keep_count(sparsity, s.M_v);
   if (K_max < k_base + s.M_x)
     return fail(DFS_ESHAPE, "dfs_select_mask: K_max=%d is below the %d kept blocks per row", K_max, k_base + s.M_x);
-  const size_t lds = size_t(s.M_v) * sizeof(uint32_t);
+  const size_t lds = size_t(s.M_v) * sizeof(uint32_t);            // the mass count keeps one key per column
+  const size_t lds_sel = lds + 256 * sizeof(uint32_t);           // the selection adds its byte histogram
   dim3 rows(unsigned(s.M), unsigned(g->heads));
   if (mode == DFS_SELECT_TOPK) {
-    select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, k_base, nullptr, nullptr, 0, mask, kv_idx, kv_cnt, K_max, k_head);
+    select_kernel<<<rows, 64, lds_sel, st>>>(score, s.M_v, s.M_x, k_base, nullptr, nullptr, 0, mask, kv_idx, kv_cnt, K_max, k_head);
   } else {
     if (!(mass > 0.0 && mass <= 1.0)) return fail(DFS_EINVAL, "dfs_select_mask: mass %g is outside (0,1]", mass);
     int32_t* k_row = static_cast<int32_t*>(ws);
@@ -204,9 +232,9 @@ int run_select_mask(const dfs_geom* g, const dfs_sizes& s, const float* score, i
     mass_count_kernel<<<dim3(unsigned(s.M_v), unsigned(g->heads)), 64, lds, st>>>(score, s.M_v, mass, k_row);
     if (mode == DFS_SELECT_MASS_HEAD) {
       head_count_kernel<<<dim3(unsigned(g->heads)), 256, 0, st>>>(k_row, s.M_v, k_base, k_cap, k_used, k_head);
-      select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, 0, k_used, nullptr, 0, mask, kv_idx, kv_cnt, K_max, nullptr);
+      select_kernel<<<rows, 64, lds_sel, st>>>(score, s.M_v, s.M_x, 0, k_used, nullptr, 0, mask, kv_idx, kv_cnt, K_max, nullptr);
     } else {
-      select_kernel<<<rows, 64, lds, st>>>(score, s.M_v, s.M_x, k_base, nullptr, k_row, k_cap, mask, kv_idx, kv_cnt, K_max, nullptr);
+      select_kernel<<<rows, 64, lds_sel, st>>>(score, s.M_v, s.M_x, k_base, nullptr, k_row, k_cap, mask, kv_idx, kv_cnt, K_max, nullptr);
     }
   }
   return launch_status("dfs_select_mask");
