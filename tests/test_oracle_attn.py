@@ -145,3 +145,28 @@ def test_tiny_workload_generator_and_recall_sanity():
     var_raster = q[0].reshape(sz["M"], w.B, w.d).var(axis=1).mean()
     var_hilbert = qp[0].reshape(sz["M"], w.B, w.d).var(axis=1).mean()
     assert var_hilbert < var_raster
+
+
+def test_bf16_rounded_weights_move_the_log_sum_exp_by_their_unit_roundoff():
+    """Why the bf16 attention kernel keeps an unrounded sum when the log-sum-exp is asked for.  Its output is
+    normalised by the sum of the softmax weights as rounded to bf16 (the weights the matrix product uses).  Taking
+    the logarithm of that sum instead of the exact one moves the log-sum-exp by up to bf16's unit roundoff
+    2^-8 = 3.9e-3 (8 significant bits, round to nearest), not by 2^-9: reached when one key dominates a row and its
+    weight falls halfway between two bf16 values, and approached (3e-3) on ordinary seeded inputs.  Computed here with
+    the oracle's logits and plain numpy rounding; nothing of the HIP path is involved."""
+    from workloads import Workload
+    from workloads.synth import round_to_bf16
+    # (a) the worst case by construction: one key, weight 1 + 2^-8 - eps relative to the reference -> rounds to 1
+    p = np.array([1.0 + 2.0 ** -8 - 2.0 ** -20], dtype=np.float32)
+    err = abs(math.log(float(round_to_bf16(p).astype(np.float64).sum())) - math.log(float(p.astype(np.float64).sum())))
+    assert 3.8e-3 < err < 2.0 ** -8
+    # (b) seeded inputs, weights relative to the row maximum
+    w = Workload("mid_bf16", 5, 12, 20, heads=1, d=128, dtype="bf16", B=128, Bs=32, sparsity=(0.6,), seed=77)
+    q, k, v = (as_f64(x) for x in make_qkv(w))
+    s = q[0] @ k[0].T / math.sqrt(w.d)
+    m = s.max(axis=1, keepdims=True)
+    pw = np.exp(s - m)
+    exact = np.log(pw.sum(axis=1))
+    rounded = np.log(round_to_bf16(pw.astype(np.float32)).astype(np.float64).sum(axis=1))
+    worst = np.abs(rounded - exact).max()
+    assert 1e-3 < worst <= 2.0 ** -8 * 1.001, worst      # far above any fp32 effect, inside the roundoff bound
