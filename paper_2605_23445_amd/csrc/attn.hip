@@ -214,8 +214,8 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   // flight into another and would wait for every outstanding load before each LDS read.  The waits
   // that are needed are the explicit vmcnt(0) + barrier pairs in the loop below.  (Loads retire in
   // order, so the compiler's own counts for its few other memory operations stay conservative.)
-  auto issue = [&](const uint16_t* base, uint16_t* stage, bool is_v, int tile) {
-    const uint64_t src = reinterpret_cast<uint64_t>(base + (int64_t(tile_block(tile)) * BM + (tile % STEPS) * KN) * D);
+  auto issue = [&](const uint16_t* base, uint16_t* stage, bool is_v, int tile, int blk) {
+    const uint64_t src = reinterpret_cast<uint64_t>(base + (int64_t(blk) * BM + (tile % STEPS) * KN) * D);
     const uint32_t lds0 = uint32_t(reinterpret_cast<uintptr_t>((LDS_PTR(void))(stage + wave * 512)));
 #pragma unroll
     for (int j = 0; j < LPW; ++j) {
@@ -266,10 +266,17 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
       for (int a = 0; a < QT; ++a) sx[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[a][kk], sx[a], 0, 0, 0);
     }
   };
-  // pad keys of a ragged block never count
-  auto mask_pads = [&](int tile, int half, f32x16 (&sx)[QT]) {
-    const int real = block_real_rows(tile_block(tile), BM, M_v, N_v, n_text);
-    if (real < BM) {
+  // pad keys of a ragged block never count.  Only two blocks can be ragged, the last video block and the last text
+  // block; their ids and real-row counts are worked out once, so that the check per half tile is two scalar compares
+  // on a block id that is already at hand (measured: the 64-bit arithmetic of the general form, twice per tile, cost
+  // 2 % of the kernel).
+  const int real_v_last = block_real_rows(M_v - 1, BM, M_v, N_v, n_text);
+  const int real_x_last = M > M_v ? block_real_rows(M - 1, BM, M_v, N_v, n_text) : BM;
+  const int ragged_v = real_v_last < BM ? M_v - 1 : -1, ragged_x = real_x_last < BM ? M - 1 : -1;
+  auto mask_pads = [&](int blk, int tile, int half, f32x16 (&sx)[QT]) {
+    if (__builtin_expect(blk == ragged_v || blk == ragged_x, 0)) {
+      asm volatile("");                               // keeps this a branch: turned into selects it would run on every half tile
+      const int real = blk == ragged_v ? real_v_last : real_x_last;
       const int base = (tile % STEPS) * KN + 32 * half;
 #pragma unroll
       for (int a = 0; a < QT; ++a)
@@ -413,6 +420,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   // read a full tile later.
   f32x16 s0[QT], s1[QT];
   u32x4 p0[QT][2], p1[QT][2];                      // probabilities as bf16 pairs: B operands of the products
+  int b_cur = 0, b_nxt = 0;                        // key blocks of tiles t and t + 1: one list lookup per tile (that of tile t + 2)
   auto tile_step = [&](auto parity, auto first, auto last, int t) {
     constexpr bool ODD = decltype(parity)::value, FIRST = decltype(first)::value, LAST = decltype(last)::value;
     uint16_t* k_cur = ODD ? sK1 : sK0;             // K(t); K(t+2) goes here
@@ -424,26 +432,34 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     // first half: products of (t-1, 1), logits of (t, 1), softmax of (t, 0)
     stage(std::integral_constant<bool, !FIRST>{}, yes{}, v_nxt, 1, p1, k_cur, 1, s1, s0, p0, alpha, moved);
     rescale(alpha, moved);
-    mask_pads(t, 1, s1);
+    mask_pads(b_cur, t, 1, s1);
     __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's parts of K(t+1) and V(t) landed
     __syncthreads();                                 // all parts landed; every wave is past the first half of tile t
+    int b_new = b_nxt;
     if (!LAST) {
-      if (t + 2 < n_tiles) issue(kh, k_cur, false, t + 2);
-      issue(vh, v_nxt, true, t + 1);
+      if (t + 2 < n_tiles) {
+        b_new = tile_block(t + 2);
+        issue(kh, k_cur, false, t + 2, b_new);
+      }
+      issue(vh, v_nxt, true, t + 1, b_nxt);
     }
     // second half: products of (t, 0), logits of (t+1, 0), softmax of (t, 1)
     stage(yes{}, std::integral_constant<bool, !LAST>{}, v_cur, 0, p0, k_nxt, 0, s0, s1, p1, alpha, moved);
     rescale(alpha, moved);
-    if (!LAST) mask_pads(t + 1, 0, s0);
+    if (!LAST) mask_pads(b_nxt, t + 1, 0, s0);
+    b_cur = b_nxt;
+    b_nxt = b_new;
   };
   if (n_tiles > 0) {
-    issue(kh, sK0, false, 0);
-    issue(vh, sV0, true, 0);
+    b_cur = tile_block(0);
+    b_nxt = n_tiles > 1 ? tile_block(1) : b_cur;
+    issue(kh, sK0, false, 0, b_cur);
+    issue(vh, sV0, true, 0, b_cur);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    if (n_tiles > 1) issue(kh, sK1, false, 1);
+    if (n_tiles > 1) issue(kh, sK1, false, 1, b_nxt);
     logits(sK0, 0, s0);
-    mask_pads(0, 0, s0);
+    mask_pads(b_cur, 0, 0, s0);
     if (n_tiles == 1) {
       tile_step(no{}, yes{}, yes{}, 0);
     } else {
