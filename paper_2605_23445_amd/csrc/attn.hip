@@ -214,9 +214,15 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
   // flight into another and would wait for every outstanding load before each LDS read.  The waits
   // that are needed are the explicit vmcnt(0) + barrier pairs in the loop below.  (Loads retire in
   // order, so the compiler's own counts for its few other memory operations stay conservative.)
+  // LDS addresses of this wave's first chunk in each tile buffer, as scalars, once (taken from a vector register
+  // inside the loop they cost a vector-to-scalar hand-over per tile)
+  auto lds_base = [&](uint16_t* buf) {
+    return __builtin_amdgcn_readfirstlane(uint32_t(reinterpret_cast<uintptr_t>((LDS_PTR(void))(buf + wave * 512))));
+  };
+  const uint32_t lds_k0 = lds_base(sK0), lds_k1 = lds_base(sK1), lds_v0 = lds_base(sV0), lds_v1 = lds_base(sV1);
   auto issue = [&](const uint16_t* base, uint16_t* stage, bool is_v, int tile, int blk) {
     const uint64_t src = reinterpret_cast<uint64_t>(base + (int64_t(blk) * BM + (tile % STEPS) * KN) * D);
-    const uint32_t lds0 = uint32_t(reinterpret_cast<uintptr_t>((LDS_PTR(void))(stage + wave * 512)));
+    const uint32_t lds0 = stage == sK0 ? lds_k0 : stage == sK1 ? lds_k1 : stage == sV0 ? lds_v0 : lds_v1;
 #pragma unroll
     for (int j = 0; j < LPW; ++j) {
       const int P = is_v ? PV : PK;
@@ -224,7 +230,7 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
       const uint64_t sj = src + uint64_t(j / P) * (P * RJ) * D * 2;
       const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(sj)), hi = __builtin_amdgcn_readfirstlane(uint32_t(sj >> 32));
       const uint64_t sbase = (uint64_t(hi) << 32) | lo;
-      const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + uint32_t(j * NW * 1024));
+      const uint32_t lds = lds0 + uint32_t(j * NW * 1024);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
     }
   };
