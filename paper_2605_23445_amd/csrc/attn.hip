@@ -332,7 +332,8 @@ attn_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
         for (int i = 0; i < 16; ++i) sn[a][i] = 0.f;
     }
-    constexpr int AHEAD = 2;                          // fragments requested ahead of their matrix instruction
+    constexpr int AHEAD = 3;                          // fragments requested ahead of their matrix instruction (2: 1 % slower;
+                                                      // 4 needs two registers more than there are)
 #pragma unroll
     for (int f = 0; f < AHEAD; ++f) load(f);
     __builtin_amdgcn_sched_barrier(0);
