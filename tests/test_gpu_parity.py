@@ -496,6 +496,61 @@ def test_source_order_variants_are_bit_identical(w):
     assert torch.equal(lse[:, real].view(torch.int32), lse2[:, real].view(torch.int32))
 
 
+def _random_geometries(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        B = int(rng.choice([64, 128]))
+        r = int(rng.choice([1, 2, 4, 8]))
+        d = int(rng.choice([64, 128]))
+        T, H, W = int(rng.integers(1, 7)), int(rng.integers(1, 20)), int(rng.integers(1, 24))
+        n_text = int(rng.choice([0, 0, 1, 37, 64, 129]))
+        heads = int(rng.integers(1, 4))
+        sp = float(rng.choice([0.0, 0.3, 0.5, 0.8, 0.97]))
+        out.append(Workload(f"rnd{i}_{T}x{H}x{W}+{n_text}_h{heads}_d{d}_B{B}_r{r}_s{sp}", T, H, W, heads=heads, d=d, dtype="bf16", B=B, Bs=B // r,
+                            sparsity=(sp,), seed=500 + i, n_text=n_text, sinks_per_frame=int(rng.integers(0, 3))))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_geometries(16, 2024), ids=lambda w: w.name)
+def test_random_small_geometries_end_to_end(w):
+    """Seeded random small geometries (grids down to a single token, every block and sub-block size, both head
+    dimensions, with and without text rows, keep ratios from one block to all): Algorithm 1 in one call against the
+    oracle - permutation bit-exact, mask equal to the oracle's selection on the GPU's scores, scores within tolerance,
+    output within the bf16 bars under the same mask."""
+    say(f"random geometry {w.name}")
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v, perm_pad_o, inv_o, blk_valid = _oracle_inputs(w)
+    perm_pad, inv, blk_valid_d = G.gpu_perm(g)
+    assert np.array_equal(perm_pad.cpu().numpy(), perm_pad_o) and np.array_equal(inv.cpu().numpy(), inv_o)
+    assert np.array_equal(blk_valid_d.cpu().numpy(), blk_valid)
+    qd, kd, vd = (G.to_dev(x) for x in (q, k, v))
+    sp = w.sparsity[0]
+    K_max = P.dfs_keep_count(sp, sz["M_v"]) + sz["M_x"]
+    st = P.MaskState(torch.full((w.heads, sz["M"], K_max), -1, dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"]), dtype=torch.int32, device="cuda"),
+                     torch.zeros((w.heads, sz["M"], sz["M"]), dtype=torch.uint8, device="cuda"), None, K_max)
+    ws = G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_FORWARD_BF16))
+    o = torch.full_like(qd, float("nan"))
+    P.dfs_forward(g, dt, qd, kd, vd, perm_pad, inv, True, P.DFS_SELECT_TOPK, sp, 0.0, st, 1.0 / math.sqrt(w.d), o, ws)
+    torch.cuda.synchronize()
+    qp_o, kp_o, vp_o = (O.permute(as_f64(x), perm_pad_o) for x in (q, k, v))
+    qp, kp = (G.gpu_permute(g, dt, x, perm_pad) for x in (qd, kd))
+    score = G.gpu_score(g, dt, qp, kp).cpu().numpy()
+    want_score = O.block_score(qp_o, kp_o, sz["N_v"], w.B, w.Bs)
+    assert np.abs(score - want_score).max() <= SCORE_TOL * sz["r"]
+    mask_o, kk = O.select_topk(score, sp, sz["M_x"])
+    mask = st.mask.cpu().numpy()
+    assert np.array_equal(mask, mask_o)
+    want, _ = O.sparse_attn(qp_o, kp_o, vp_o, mask, blk_valid, w.B)
+    got = G.as_f64_dev(o)
+    assert not np.isnan(got).any()
+    err = np.abs(got - O.unpermute(want, inv_o))
+    say(f"  M {sz['M']} k {kk}: output max err {err.max():.3e} mean err {err.mean():.3e}")
+    assert err.max() <= BF16_MAX and err.mean() <= BF16_MEAN
+
+
 # ---------------------------------------------------------------------------- reruns
 
 @pytest.mark.parametrize("w", [MID_BF16, MID_D64, MID_F32, CONFIGS["wan"].with_heads(6)], ids=lambda w: w.name)
