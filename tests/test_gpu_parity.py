@@ -393,6 +393,36 @@ def test_full_size_workloads(name, oracle_heads):
         _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, blocks, heads_idx=list(oracle_heads))
 
 
+@pytest.mark.parametrize("Bs", [16, 64, 128])
+def test_full_size_sub_block_sizes(Bs):
+    """Table 4's sub-block sizes at the full 75 600-token shape (the benchmark configuration uses 32; 16 is the
+    paper's default, 128 means no sub-blocks): scores of three heads against the fp64 oracle, the 90 % selection
+    bit-exact against the oracle's selection on the same scores, and the attention output under that mask on
+    sampled query blocks."""
+    from dataclasses import replace
+    w = replace(CONFIGS["wan"].with_heads(3), Bs=Bs, sparsity=(0.9,))
+    sz = derived_sizes(w)
+    say(f"full size wan, Bs {Bs}: r {sz['r']} M_s {sz['M_v'] * sz['r']}")
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    perm_pad_o, inv_o, blk_valid = O.hilbert_perm(w.T, w.H, w.W, w.n_text, w.B)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    q, k, v = make_qkv(w)
+    qp, kp, vp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k, v))
+    score = G.gpu_score(g, dt, qp, kp)
+    score_np = score.cpu().numpy()
+    score64 = O.block_score(O.permute(as_f64(q), perm_pad_o), O.permute(as_f64(k), perm_pad_o), sz["N_v"], w.B, w.Bs)
+    err = np.abs(score_np - score64).max()
+    say(f"  score max err {err:.3e} (bound {SCORE_TOL * sz['r']:.1e})")
+    assert err <= SCORE_TOL * sz["r"]
+    st = G.gpu_select(g, score, P.DFS_SELECT_TOPK, 0.9)
+    mask = st.mask.cpu().numpy()
+    mask_o, kk = O.select_topk(score_np, 0.9, sz["M_x"])
+    assert np.array_equal(mask, mask_o) and kk == 60
+    loose = _check_p3(score64, mask, kk, sz["M_v"], SCORE_TOL * sz["r"])
+    say(f"  masks bit-exact on GPU scores; rows at the fp64 threshold: {loose}")
+    _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, _sample_blocks(sz["M_v"], sz["M"], w.seed, n=6), heads_idx=[0, 2])
+
+
 def test_full_size_caching_schedule():
     """The mask-caching workload at full size (75 600 tokens, 40 heads) through the one-call entry point: the
     first steps of its schedule (refresh at steps 0 and 5 with the adaptive per-head ratio, reuse in between)
