@@ -423,6 +423,32 @@ def test_full_size_sub_block_sizes(Bs):
     _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, _sample_blocks(sz["M_v"], sz["M"], w.seed, n=6), heads_idx=[0, 2])
 
 
+def test_full_size_per_row_adaptive_masks_with_text():
+    """Per-row adaptive masks (every query block its own keep count from the mass rule) at the full 118 800-token
+    shape with its 256 appended text tokens, three heads: keep counts and masks bit-exact against the oracle's
+    selection on the same scores, then the attention kernel on these lists of unequal length (video rows keep
+    their own count plus the text blocks, text rows keep everything) on sampled query blocks."""
+    w = CONFIGS["hunyuan"].with_heads(3)
+    sz = derived_sizes(w)
+    say(f"full size hunyuan, per-row mass rule: N {sz['N']} M {sz['M']}")
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    perm_pad_o, inv_o, blk_valid = O.hilbert_perm(w.T, w.H, w.W, w.n_text, w.B)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    q, k, v = make_qkv(w)
+    qp, kp, vp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k, v))
+    score = G.gpu_score(g, dt, qp, kp)
+    score_np = score.cpu().numpy()
+    for mass, cap in ((0.9, 0.95), (0.5, 0.98)):
+        st = G.gpu_select(g, score, P.DFS_SELECT_MASS_ROW, cap, mass=mass)
+        mask = st.mask.cpu().numpy()
+        mask_o, k_row_o = O.select_mass_row(score_np, mass, cap, sz["M_x"])
+        cnt = st.kv_cnt.cpu().numpy()
+        assert np.array_equal(cnt[:, :sz["M_v"]], k_row_o + sz["M_x"]) and np.all(cnt[:, sz["M_v"]:] == sz["M"])
+        assert np.array_equal(mask, mask_o)
+        say(f"  mass {mass} cap {cap}: keep counts {k_row_o.min()}..{k_row_o.max()} (mean {k_row_o.mean():.1f}), masks bit-exact")
+        _compare_attention(w, g, dt, qp, kp, vp, st, mask, blk_valid, _sample_blocks(sz["M_v"], sz["M"], w.seed, n=5), heads_idx=[0, 2])
+
+
 def test_full_size_caching_schedule():
     """The mask-caching workload at full size (75 600 tokens, 40 heads) through the one-call entry point: the
     first steps of its schedule (refresh at steps 0 and 5 with the adaptive per-head ratio, reuse in between)
