@@ -243,7 +243,7 @@ def main():
     r_sub = w.B // w.Bs
     M_s = M_v * r_sub
     score_alg = 2.0 * w.heads * (sz["N"] if fused else N_pad) * w.d * e + w.heads * M_v * M_v * 4.0
-    planes = 2.0 * w.heads * M_s * 3 * w.d * 2
+    planes = 2.0 * w.heads * M_s * 2 * w.d * 2          # Q_hat and K_hat as two fp16 planes each
     score_moved = score_alg + (w.heads * N_pad * w.d * e if fused else 0.0) + 2 * planes + 2.0 * w.heads * M_v * M_s * 4
     select_bytes = w.heads * M_v * M_v * 4.0 + w.heads * M * (K_max + 1) * 4.0
     out = {
@@ -274,7 +274,7 @@ def main():
         "score_gbs": score_alg / (stage_ms["block_score"] * 1e-3) / 1e9,
         "score_hbm_frac": score_alg / (stage_ms["block_score"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "score_moved_gbs": score_moved / (stage_ms["block_score"] * 1e-3) / 1e9,
-        "score_note": "block_score = pooling (HBM-bound) + the sub-block logits as six bf16 products per fp32 logit on the matrix "
+        "score_note": "block_score = pooling (HBM-bound) + the sub-block logits as three fp16 products per fp32 logit on the matrix "
                       "cores + fold; the stage is bound by that contraction, not by memory",
         "select_gbs": select_bytes / (stage_ms["select_mask"] * 1e-3) / 1e9,
         "score_plus_select_ms": stage_ms["block_score"] + stage_ms["select_mask"],

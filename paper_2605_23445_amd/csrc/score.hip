@@ -1,18 +1,19 @@
 // Hierarchical block scoring (paper Sec. 5.2; Algorithm 1 step 2; Eq. 2 and Eq. 8).
 //
 //   pool_kernel   : Q_hat, K_hat = mean over the real rows of each sub-block, an HBM stream.  The fp32
-//                   means (Q_hat already times 1/sqrt(d)) are stored split into three bf16 terms
-//                   x = hi + mid + lo, which together carry the 24 bits of the fp32 value.
+//                   means (Q_hat already times 1/sqrt(d)) are scaled, four consecutive sub-blocks at a time,
+//                   by the power of two that brings their largest magnitude to 2^11..2^12, and stored as two
+//                   fp16 terms x = hi + lo, which together carry 22 bits of the value.
 //   score_lse_kernel / score_fold_kernel : S_hat[u,v] = sum over the r x r sub-block pairs of
 //                   softmax(Q_hat K_hat^T / sqrt(d)).  The sub-block attention matrix A_hat is never stored.
 //                   One pass over the contraction: per (query sub-block, key block) the base-2 log of the
-//                   summed exponentials of the block's key sub-blocks (which needs no row reference) and per
-//                   query sub-block the row log-sum-exp; a second, memory-bound kernel turns these into
-//                   probabilities and folds the r query sub-blocks of a query block.  The logits run on the
-//                   bf16 matrix cores as six partial products hi.hi + hi.mid + mid.hi + hi.lo + lo.hi +
-//                   mid.mid with fp32 accumulation: every bf16 product is exact in fp32 and the dropped terms
-//                   are below 2^-23 of the result, so the logits are as accurate as an fp32 contraction at
-//                   several times its speed (the mask decision that follows stays an fp32 one).
+//                   summed exponentials of the block's key sub-blocks and per query sub-block the row
+//                   log-sum-exp; a second, memory-bound kernel turns these into probabilities and folds the r
+//                   query sub-blocks of a query block.  The logits run on the fp16 matrix cores as three
+//                   partial products hi.hi + hi.lo + lo.hi with fp32 accumulation: every fp16 product is exact
+//                   in fp32 and the dropped lo.lo term is below 2^-22 of the result, so the logits are as
+//                   accurate as an fp32 contraction at several times its speed (the mask decision that
+//                   follows stays an fp32 one); the scaling is undone, exactly, on the fp32 result.
 #include "common.h"
 
 namespace dfs {
@@ -22,24 +23,43 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // ------------------------------------------------------------------------------------ pooling
 
-// x -> (hi, mid, lo) with hi = bf16(x), mid = bf16(x - hi), lo = bf16(x - hi - mid); the subtractions are exact.
-__device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
-  hi = f32_to_bf16(x);
-  const float r1 = x - bf16_to_f32(hi);
-  mid = f32_to_bf16(r1);
-  const float r2 = r1 - bf16_to_f32(mid);
-  lo = f32_to_bf16(r2);
+// x (already scaled so that its group's largest magnitude is in [2^11, 2^12)) -> (hi, lo) with hi = fp16(x),
+// lo = fp16(x - hi).  The subtraction is exact and |x - hi| <= 2^-11 |x|, so x = hi + lo to within 2^-22 |x| as long
+// as lo is a normal fp16 number, which it is for |x| >= 2^-3: an element more than 2^14 times smaller than the
+// largest of its group is kept to 2^-25 absolute instead, i.e. to 2^-36 of that largest one.
+__device__ __forceinline__ void split2(float x, uint16_t& hi, uint16_t& lo) {
+  const _Float16 h = (_Float16)x;
+  const _Float16 l = (_Float16)(x - (float)h);
+  hi = __builtin_bit_cast(uint16_t, h);
+  lo = __builtin_bit_cast(uint16_t, l);
+}
+// Rows are scaled in groups of four consecutive sub-blocks (the four waves of a pooling work-group) by a power of
+// two that brings the group's largest magnitude into [2^11, 2^12); `down` is the inverse.  Powers of two: exact.
+constexpr int SHIFT_MAX = 100;                 // keeps both factors finite for groups of vanishing magnitude
+__device__ __forceinline__ void group_scale(float gmax, float& up, float& down) {
+  up = 1.0f; down = 1.0f;
+  if (gmax > 0.f && gmax < INFINITY) {
+    int ex;
+    (void)frexpf(gmax, &ex);                   // gmax = m 2^ex, m in [0.5, 1)
+    int sh = 12 - ex;
+    sh = sh > SHIFT_MAX ? SHIFT_MAX : (sh < -SHIFT_MAX ? -SHIFT_MAX : sh);
+    up = ldexpf(1.0f, sh);
+    down = ldexpf(1.0f, -sh);
+  }
 }
 
 // One wave per sub-block.  Lanes of a row sit side by side (16 bytes each); several rows are in
 // flight per load; partial sums of the row groups are folded with cross-lane exchanges.
-// Output row layout: [3][D] bf16 (hi, mid, lo planes).
+// Output row layout: [2][D] fp16 (hi, lo planes) of the row times its group's scale; the inverse scale of
+// group s / 4 goes to q_down / k_down.
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_perm, const void* __restrict__ k_perm,
                                                    uint16_t* __restrict__ q_hat, uint16_t* __restrict__ k_hat,
+                                                   float* __restrict__ q_down, float* __restrict__ k_down,
                                                    const int32_t* __restrict__ q_index, void* __restrict__ k_out, int64_t N_src,
                                                    int64_t N_pad, int64_t N_v, int Bs, int M_s, float q_scale) {
   constexpr int EPL = BF16 ? 8 : 4;           // elements per lane (16 bytes)
@@ -51,7 +71,8 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
   // written out in the reordered layout on the way (pads as zeros), which spares the reorder pass of K.  The
   // sub-blocks behind the video segment (text rows) are then copied only.
   const bool k_copy = blockIdx.z == 1 && k_out != nullptr;
-  if (s >= M_s && !(k_copy && int64_t(s) * Bs < N_pad)) return;
+  const bool pooled = s < M_s;                               // this wave has a sub-block to pool
+  const bool busy = pooled || (k_copy && int64_t(s) * Bs < N_pad);
   const int head = blockIdx.y;
   const void* src = blockIdx.z == 0 ? q_perm : k_perm;
   uint16_t* dst = blockIdx.z == 0 ? q_hat : k_hat;
@@ -67,7 +88,7 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
   const bool gather = q_index != nullptr && (blockIdx.z == 0 || k_copy);
   const u32x4* base = reinterpret_cast<const u32x4*>(src) + (gather ? int64_t(head) * N_src * TPR : (int64_t(head) * N_pad + row0) * TPR) + c;
   u32x4* copy = k_copy ? reinterpret_cast<u32x4*>(k_out) + (int64_t(head) * N_pad + row0) * TPR + c : nullptr;
-  const int rows = k_copy ? Bs : cnt;         // a copy covers the pad rows of the sub-block as well
+  const int rows = !busy ? 0 : k_copy ? Bs : cnt;   // a copy covers the pad rows of the sub-block as well
   for (int i = rg; i < rows; i += RPP) {
     int64_t from = i;
     bool real = true;
@@ -91,23 +112,37 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
       for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(v[e]);
     }
   }
-  if (s >= M_s) return;                        // copied only
 #pragma unroll
   for (int off = TPR; off < 64; off <<= 1) {
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
   }
-  if (rg == 0) {
-    const float inv = cnt > 0 ? (blockIdx.z == 0 ? q_scale : 1.0f) / float(cnt) : 0.f;
-    uint16_t* o = dst + (int64_t(head) * M_s + s) * (3 * D) + c * EPL;
-    uint16_t hi[EPL], mid[EPL], lo[EPL];
+  // every lane now holds the column sums of its 16 bytes of the row; the row's largest magnitude, then the group's
+  const float inv = pooled && cnt > 0 ? (blockIdx.z == 0 ? q_scale : 1.0f) / float(cnt) : 0.f;
+  float mx = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) split3(acc[e] * inv, hi[e], mid[e], lo[e]);
+  for (int e = 0; e < EPL; ++e) {
+    acc[e] *= inv;
+    mx = fmaxf(mx, fabsf(acc[e]));
+  }
+#pragma unroll
+  for (int off = 1; off < TPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  __shared__ float s_max[4];
+  if (lane == 0) s_max[threadIdx.x >> 6] = mx;
+  __syncthreads();                             // reached by all four waves: none has left the kernel
+  if (!pooled) return;                         // copied only, or beyond the last sub-block
+  float up, down;
+  group_scale(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3])), up, down);
+  if (threadIdx.x == 0) (blockIdx.z == 0 ? q_down : k_down)[int64_t(head) * ((M_s + 3) / 4) + blockIdx.x] = down;
+  if (rg == 0) {
+    uint16_t* o = dst + (int64_t(head) * M_s + s) * (2 * D) + c * EPL;
+    uint16_t hi[EPL], lo[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) split2(acc[e] * up, hi[e], lo[e]);
 #pragma unroll
     for (int e = 0; e < EPL; e += 2) {
       *reinterpret_cast<uint32_t*>(o + e) = uint32_t(hi[e]) | (uint32_t(hi[e + 1]) << 16);
-      *reinterpret_cast<uint32_t*>(o + D + e) = uint32_t(mid[e]) | (uint32_t(mid[e + 1]) << 16);
-      *reinterpret_cast<uint32_t*>(o + 2 * D + e) = uint32_t(lo[e]) | (uint32_t(lo[e + 1]) << 16);
+      *reinterpret_cast<uint32_t*>(o + D + e) = uint32_t(lo[e]) | (uint32_t(lo[e + 1]) << 16);
     }
   }
 }
@@ -115,6 +150,12 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
 // ------------------------------------------------------------------------------------ scoring
 
 constexpr float LSE_START = -1.0e30f;          // finite stand-in for "nothing seen yet" (keeps differences finite)
+
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 
 // Running base-2 log-sum-exp (reference m, sum z of 2^(x - m)): add one term, merge two partial sums.
 __device__ __forceinline__ void lse_add(float& m, float& z, float x) {
@@ -138,9 +179,9 @@ __device__ __forceinline__ void lse_merge(float& m, float& z, float m2, float z2
 // T into probabilities and folds the R query sub-blocks of a query block.
 template <int D, int R>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, float* __restrict__ tt,
-                 float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit) {
-  constexpr int RS = 3 * D;                   // elements of a centroid row (hi, mid, lo planes)
+score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, const float* __restrict__ q_down,
+                 const float* __restrict__ k_down, float* __restrict__ tt, float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit) {
+  constexpr int RS = 2 * D;                   // elements of a centroid row (hi, lo planes)
   constexpr int RSP = RS + 8;                 // LDS row stride: 16 bytes of skew keep the row-per-lane reads conflict-free
   constexpr int KS = D / 16;                  // product steps of 16 features
   constexpr int CPT = 32 * RS / 8 / 256;      // 16-byte chunks of a key tile per thread (6 at d=128)
@@ -154,17 +195,20 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
   const uint16_t* qh = q_hat + int64_t(head) * M_s * RS;
   const uint16_t* kh = k_hat + int64_t(head) * M_s * RS;
 
-  // Query centroids as the B operand: lane (n, half) holds row i0 + n, features 16 kk + 8 half .. + 7, three planes.
-  bf16x8 bq[3][KS];
+  // Query centroids as the B operand: lane (n, half) holds row i0 + n, features 16 kk + 8 half .. + 7, two planes.
+  const int G4 = (M_s + 3) / 4;               // scale groups (four consecutive sub-blocks) per head
+  f16x8 bq[2][KS];
+  float q_dn = 1.0f;                          // inverse scale of this lane's query row
   {
     const int row = i0 + n;
+    if (row < M_s) q_dn = q_down[int64_t(head) * G4 + row / 4];
 #pragma unroll
-    for (int p = 0; p < 3; ++p)
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (row < M_s) v = *reinterpret_cast<const u32x4*>(qh + int64_t(row) * RS + p * D + 16 * kk + 8 * half);
-        bq[p][kk] = __builtin_bit_cast(bf16x8, v);
+        bq[p][kk] = __builtin_bit_cast(f16x8, v);
       }
   }
   const int n_tiles = (n_live + 31) / 32;     // key sub-blocks at or beyond n_live are empty
@@ -189,68 +233,97 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
       *reinterpret_cast<u32x4*>(&s_k[buf][(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = stage[i];
     }
   };
-  // transposed logits of the 32 x 32 tile: c[i] = <k_hat[row 8 (i/4) + 4 half + i%4 of the tile], q_hat[i0 + n]>
-  auto logit_tile = [&](int buf) {
-    // three accumulators, so that consecutive matrix instructions never wait for each other's result
-    f32x16 sa = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 sb = sa, big = sa;
+  // transposed logits of the 32 x 32 tile: c[i] = <k_hat[row 8 (i/4) + 4 half + i%4 of the tile], q_hat[i0 + n]>.
+  // Registers 4 g .. 4 g + 3 of a lane are four consecutive key rows, one scale group: dn[g] undoes the scaling of
+  // that group and of the query row.
+  auto logit_tile = [&](int buf, const float (&dn)[4]) {
+    // hi.hi, hi.lo and lo.hi products (lo.lo is below 2^-22 of the result) with fp32 accumulation, dealt to two
+    // accumulators in turn so that no matrix instruction waits for the one before it
+    f32x16 a0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 a1 = a0;
     const uint16_t* krow = &s_k[buf][n * RSP + 8 * half];
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
-      const bf16x8 am = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
-      const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(krow + 2 * D + 16 * kk));
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[2][kk], sa, 0, 0, 0);     // hi.lo
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bq[0][kk], sb, 0, 0, 0);     // lo.hi
-      big = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[0][kk], big, 0, 0, 0);   // hi.hi
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bq[1][kk], sa, 0, 0, 0);     // mid.mid
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bq[1][kk], sb, 0, 0, 0);     // hi.mid
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bq[0][kk], sa, 0, 0, 0);     // mid.hi
+    for (int kk = 0; kk < KS; kk += 2) {
+      const f16x8 ah = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
+      const f16x8 al = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
+      const f16x8 bh = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk + 16));
+      const f16x8 bl = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk + 16));
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bq[0][kk], a0, 0, 0, 0);       // hi.hi
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bq[1][kk], a1, 0, 0, 0);       // hi.lo
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bq[0][kk], a0, 0, 0, 0);       // lo.hi
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, bq[0][kk + 1], a1, 0, 0, 0);
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, bq[1][kk + 1], a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, bq[0][kk + 1], a1, 0, 0, 0);
     }
-    const f32x16 small = sa + sb;
-    return big + small;
+    f32x16 c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[i] = (a0[i] + a1[i]) * dn[i / 4];
+    return c;
   };
 
   float m_row = LSE_START, z_row = 0.f;       // this lane's share of the row log-sum-exp of query sub-block i0 + n
   const int q_row = i0 + n;
   float* tt_h = tt + int64_t(head) * M_v * M_s;
+  // inverse scales for the four row groups of tile t that this lane's registers cover, times the query row's
+  auto load_dn = [&](int t, float (&dn)[4]) {
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {            // scale group of key rows 32 t + 8 gq + 4 half .. + 3
+      const int grp = 8 * t + 2 * gq + half;
+      dn[gq] = (grp < G4 ? k_down[int64_t(head) * G4 + grp] : 1.0f) * q_dn;
+    }
+  };
   if (t_begin < t_end) {
+    // Tile t + 1 is written to LDS right after the matrix work of tile t, and only then the loads of tile t + 2
+    // are issued: they have a whole iteration to land, with one set of staging registers.
+    float dn_next[4];
+    load_dn(t_begin, dn_next);
     fetch(t_begin);
     commit(0);
+    if (t_begin + 1 < t_end) fetch(t_begin + 1);
     __syncthreads();
     for (int t = t_begin; t < t_end; ++t) {
       const int buf = (t - t_begin) & 1;
-      if (t + 1 < t_end) fetch(t + 1);
-      f32x16 c = logit_tile(buf);
-      if (t + 1 < t_end) commit(buf ^ 1);     // the other buffer was last read before the previous barrier
-      if (t * 32 + 32 > n_live) {             // ragged end: key sub-blocks without rows count for nothing
+      float dn[4];
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) dn[gq] = dn_next[gq];
+      f32x16 c = logit_tile(buf, dn);
+      if (t + 1 < t_end) {
+        commit(buf ^ 1);                      // the other buffer was last read before the previous barrier
+        load_dn(t + 1, dn_next);
+      }
+      if (t + 2 < t_end) fetch(t + 2);
+      if (__builtin_expect(t * 32 + 32 > n_live, 0)) {   // ragged end: key sub-blocks without rows count for nothing
+        asm volatile("");                     // keeps this a branch: as selects it would run on every tile
 #pragma unroll
         for (int i = 0; i < 16; ++i)
           if (t * 32 + 8 * (i / 4) + 4 * half + (i % 4) >= n_live) c[i] = -INFINITY;
       }
+      // One reference for the whole tile: the running row maximum including this tile (finite from the start, so
+      // no difference is ever inf - inf; masked logits give 2^-inf = 0).  R == 8: a key block is split over the two
+      // lane halves, which therefore share the reference.
+      float mt = vmax3(c[0], c[1], c[2]);
+#pragma unroll
+      for (int i = 3; i < 15; i += 2) mt = vmax3(mt, c[i], c[i + 1]);
+      mt = fmaxf(mt, c[15]);
+      if (R == 8) mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float m_new = fmaxf(m_row, mt);
+      z_row *= __builtin_amdgcn_exp2f(m_row - m_new);
+      m_row = m_new;
       // fold the key sub-blocks of each key block: groups of G consecutive registers
 #pragma unroll
       for (int gi = 0; gi < 16 / G; ++gi) {
-        float mg = c[gi * G];
-#pragma unroll
-        for (int e = 1; e < G; ++e) mg = fmaxf(mg, c[gi * G + e]);
         float sg = 0.f;
-        const float ref = mg == -INFINITY ? 0.f : mg;
 #pragma unroll
-        for (int e = 0; e < G; ++e) sg += __builtin_amdgcn_exp2f(c[gi * G + e] - ref);
-        float tv = mg == -INFINITY ? -INFINITY : mg + __builtin_amdgcn_logf(sg);
+        for (int e = 0; e < G; ++e) sg += __builtin_amdgcn_exp2f(c[gi * G + e] - m_new);
+        z_row += sg;                           // this lane's own share of the row sum
+        if (R == 8) sg += __shfl_xor(sg, 32, 64);
+        // a block whose sum vanishes against the row maximum (below 2^-126 of it) scores nothing: log2(0) = -inf
+        const float tv = G == 1 ? c[gi] : m_new + __builtin_amdgcn_logf(sg);
         // key sub-block of the group's first register: 8 (first / 4) + 4 half + first % 4
         const int first = gi * G;
         const int ks = t * 32 + 8 * (first / 4) + 4 * half + (first % 4);
-        if (R == 8) {                          // the other half of the block sits in lane ^ 32
-          const float other = __shfl_xor(tv, 32, 64);
-          float m2 = fmaxf(tv, other);
-          tv = m2 == -INFINITY ? -INFINITY
-                               : m2 + __builtin_amdgcn_logf(__builtin_amdgcn_exp2f(tv - m2) + __builtin_amdgcn_exp2f(other - m2));
-        }
         const int v = ks / R;
         if ((R != 8 || half == 0) && v < M_v && q_row < M_s) tt_h[int64_t(v) * M_s + q_row] = tv;
-        if (R != 8 || half == 0) lse_add(m_row, z_row, tv);
       }
       __syncthreads();                        // tile t has been read by every wave; tile t + 1 is in LDS
     }
@@ -306,10 +379,13 @@ __global__ void __launch_bounds__(256) score_fold_kernel(const float* __restrict
   }
 }
 
-// Workspace: Q_hat, K_hat (three bf16 planes each), T [heads][M_v][M_s] fp32, row log-sum-exp
-// [heads][KSPLIT_MAX][M_s] fp32.
+// Workspace: Q_hat, K_hat (two fp16 planes each, followed by the inverse scales of their row groups),
+// T [heads][M_v][M_s] fp32, row log-sum-exp [heads][KSPLIT_MAX][M_s] fp32.
 constexpr int KSPLIT_MAX = 4;
-static size_t ws_hat_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_s * 3 * g->d * sizeof(uint16_t)); }
+static size_t ws_planes_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_s * 2 * g->d * sizeof(uint16_t)); }
+static size_t ws_hat_bytes(const dfs_geom* g, const dfs_sizes& s) {
+  return ws_planes_bytes(g, s) + align256(size_t(g->heads) * ((s.M_s + 3) / 4) * sizeof(float));
+}
 static size_t ws_tt_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_v * s.M_s * sizeof(float)); }
 static size_t ws_lse_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * KSPLIT_MAX * s.M_s * sizeof(float)); }
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s) {
@@ -332,12 +408,12 @@ static int choose_ksplit(int64_t groups_times_heads, int n_tiles) {
 }
 
 template <int D, int R>
-static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* q_hat, const uint16_t* k_hat, float* tt, float* lse,
-                         float* score, int n_live, hipStream_t st) {
+static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* q_hat, const uint16_t* k_hat, const float* q_down,
+                         const float* k_down, float* tt, float* lse, float* score, int n_live, hipStream_t st) {
   const int groups = (s.M_s + 127) / 128, n_tiles = (n_live + 31) / 32;
   const int ksplit = choose_ksplit(int64_t(groups) * g->heads, n_tiles);
   const int per = (n_tiles + ksplit - 1) / ksplit;
-  score_lse_kernel<D, R><<<dim3(unsigned(groups * ksplit), unsigned(g->heads)), 256, 0, st>>>(q_hat, k_hat, tt, lse, s.M_s, s.M_v, n_live,
+  score_lse_kernel<D, R><<<dim3(unsigned(groups * ksplit), unsigned(g->heads)), 256, 0, st>>>(q_hat, k_hat, q_down, k_down, tt, lse, s.M_s, s.M_v, n_live,
                                                                                               per, ksplit);
   const unsigned tb = unsigned((s.M_v + 31) / 32);
   score_fold_kernel<R><<<dim3(tb, tb, unsigned(g->heads)), 256, 0, st>>>(tt, lse, score, s.M_s, s.M_v, n_live, ksplit);
@@ -350,6 +426,8 @@ int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   char* base = static_cast<char*>(ws);
   uint16_t* q_hat = reinterpret_cast<uint16_t*>(base);
   uint16_t* k_hat = reinterpret_cast<uint16_t*>(base + ws_hat_bytes(g, s));
+  float* q_down = reinterpret_cast<float*>(base + ws_planes_bytes(g, s));
+  float* k_down = reinterpret_cast<float*>(base + ws_hat_bytes(g, s) + ws_planes_bytes(g, s));
   float* tt = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s));
   float* lse = reinterpret_cast<float*>(base + 2 * ws_hat_bytes(g, s) + ws_tt_bytes(g, s));
   const int64_t pool_subs = k_out ? s.N_pad / g->Bs : s.M_s;   // with k_out the text blocks are copied as well
@@ -357,12 +435,12 @@ int run_block_score(const dfs_geom* g, const dfs_sizes& s, int dtype, const void
   const bool bf = dtype == DFS_BF16;
   // 1/sqrt(d) of Eq. 2 and the change to base 2 go into Q_hat, so that the logits come out of the contraction in base 2
   const float scale = 1.4426950408889634f / sqrtf(float(g->d));
-#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_index, k_out, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
+#define POOL(BF, DD) pool_kernel<BF, DD><<<pg, 256, 0, st>>>(q_perm, k_perm, q_hat, k_hat, q_down, k_down, q_index, k_out, s.N, s.N_pad, s.N_v, g->Bs, s.M_s, scale)
   if (g->d == 64) { if (bf) POOL(true, 64); else POOL(false, 64); }
   else            { if (bf) POOL(true, 128); else POOL(false, 128); }
 #undef POOL
   const int n_live = int((s.N_v + g->Bs - 1) / g->Bs);
-#define SCORE(DD, RR) launch_score<DD, RR>(g, s, q_hat, k_hat, tt, lse, score, n_live, st)
+#define SCORE(DD, RR) launch_score<DD, RR>(g, s, q_hat, k_hat, q_down, k_down, tt, lse, score, n_live, st)
 #define SCORE_R(DD)                                                                 \
   switch (s.r) {                                                                    \
     case 1: SCORE(DD, 1); break;                                                    \
