@@ -14,6 +14,8 @@
 //                   in fp32 and the dropped lo.lo term is below 2^-22 of the result, so the logits are as
 //                   accurate as an fp32 contraction at several times its speed (the mask decision that
 //                   follows stays an fp32 one); the scaling is undone, exactly, on the fp32 result.
+#include <type_traits>
+
 #include "common.h"
 
 namespace dfs {
@@ -157,6 +159,14 @@ __device__ __forceinline__ float vmax3(float a, float b, float c) {
   return r;
 }
 
+// The value of the other lane half (lane ^ 32) beside this lane's own, through the vector unit (a shuffle through
+// LDS would make the wave wait for every LDS read in flight).  Returns {lower half's value, upper half's value}.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  lo = __uint_as_float(sw[0]);
+  hi = __uint_as_float(sw[1]);
+}
+
 // Running base-2 log-sum-exp (reference m, sum z of 2^(x - m)): add one term, merge two partial sums.
 __device__ __forceinline__ void lse_add(float& m, float& z, float x) {
   const float mn = fmaxf(m, x);
@@ -180,7 +190,8 @@ __device__ __forceinline__ void lse_merge(float& m, float& z, float m2, float z2
 template <int D, int R>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, const float* __restrict__ q_down,
-                 const float* __restrict__ k_down, float* __restrict__ tt, float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit) {
+                 const float* __restrict__ k_down, float* __restrict__ tt, float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit,
+                 int wgs_per_head, int total_wgs, int wgs_per_xcd) {
   constexpr int RS = 2 * D;                   // elements of a centroid row (hi, lo planes)
   constexpr int RSP = RS + 8;                 // LDS row stride: 16 bytes of skew keep the row-per-lane reads conflict-free
   constexpr int KS = D / 16;                  // product steps of 16 features
@@ -189,9 +200,14 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
   __shared__ __attribute__((aligned(16))) uint16_t s_k[2][32 * RSP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, half = lane >> 5;
-  const int head = blockIdx.y;
-  const int split = blockIdx.x % ksplit;
-  const int i0 = (blockIdx.x / ksplit) * 128 + wave * 32;   // first query sub-block of this wave
+  // Work-group ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Every XCD takes a contiguous
+  // eighth of the (head, query group, key range) list, so that the work-groups resident on an XCD belong to one or
+  // two heads and that head's key centroids (re-read by every one of them) stay in its L2.
+  const int logical = (blockIdx.x % 8) * wgs_per_xcd + blockIdx.x / 8;
+  if (logical >= total_wgs) return;           // the whole work-group: no barrier has been reached yet
+  const int head = logical / wgs_per_head, in_head = logical % wgs_per_head;
+  const int split = in_head % ksplit;
+  const int i0 = (in_head / ksplit) * 128 + wave * 32;      // first query sub-block of this wave
   const uint16_t* qh = q_hat + int64_t(head) * M_s * RS;
   const uint16_t* kh = k_hat + int64_t(head) * M_s * RS;
 
@@ -216,51 +232,24 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
   const int t_end = t_begin + tiles_per_split < n_tiles ? t_begin + tiles_per_split : n_tiles;
 
   // key tile t (32 centroid rows, contiguous in memory) -> registers -> LDS
-  u32x4 stage[CPT];
+  u32x4 kreg[CPT];
   auto fetch = [&](int t) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
+      // rows at or beyond M_s re-read the last row instead (no branch): they are at or beyond n_live and masked later
       const int c = tid + i * 256;
       const int row = t * 32 + c / (RS / 8);
-      stage[i] = u32x4{0u, 0u, 0u, 0u};
-      if (row < M_s) stage[i] = *reinterpret_cast<const u32x4*>(kh + int64_t(t) * 32 * RS + int64_t(c) * 8);
+      const int from = row < M_s ? row : M_s - 1;
+      kreg[i] = *reinterpret_cast<const u32x4*>(kh + int64_t(from) * RS + (c % (RS / 8)) * 8);
     }
   };
   auto commit = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
       const int c = tid + i * 256;
-      *reinterpret_cast<u32x4*>(&s_k[buf][(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = stage[i];
+      *reinterpret_cast<u32x4*>(&s_k[buf][(c / (RS / 8)) * RSP + (c % (RS / 8)) * 8]) = kreg[i];
     }
   };
-  // transposed logits of the 32 x 32 tile: c[i] = <k_hat[row 8 (i/4) + 4 half + i%4 of the tile], q_hat[i0 + n]>.
-  // Registers 4 g .. 4 g + 3 of a lane are four consecutive key rows, one scale group: dn[g] undoes the scaling of
-  // that group and of the query row.
-  auto logit_tile = [&](int buf, const float (&dn)[4]) {
-    // hi.hi, hi.lo and lo.hi products (lo.lo is below 2^-22 of the result) with fp32 accumulation, dealt to two
-    // accumulators in turn so that no matrix instruction waits for the one before it
-    f32x16 a0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 a1 = a0;
-    const uint16_t* krow = &s_k[buf][n * RSP + 8 * half];
-#pragma unroll
-    for (int kk = 0; kk < KS; kk += 2) {
-      const f16x8 ah = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk));
-      const f16x8 al = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk));
-      const f16x8 bh = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 16 * kk + 16));
-      const f16x8 bl = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 16 * kk + 16));
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bq[0][kk], a0, 0, 0, 0);       // hi.hi
-      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bq[1][kk], a1, 0, 0, 0);       // hi.lo
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bq[0][kk], a0, 0, 0, 0);       // lo.hi
-      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, bq[0][kk + 1], a1, 0, 0, 0);
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, bq[1][kk + 1], a0, 0, 0, 0);
-      a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, bq[0][kk + 1], a1, 0, 0, 0);
-    }
-    f32x16 c;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) c[i] = (a0[i] + a1[i]) * dn[i / 4];
-    return c;
-  };
-
   float m_row = LSE_START, z_row = 0.f;       // this lane's share of the row log-sum-exp of query sub-block i0 + n
   const int q_row = i0 + n;
   float* tt_h = tt + int64_t(head) * M_v * M_s;
@@ -269,63 +258,160 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
 #pragma unroll
     for (int gq = 0; gq < 4; ++gq) {            // scale group of key rows 32 t + 8 gq + 4 half .. + 3
       const int grp = 8 * t + 2 * gq + half;
-      dn[gq] = (grp < G4 ? k_down[int64_t(head) * G4 + grp] : 1.0f) * q_dn;
+      dn[gq] = k_down[int64_t(head) * G4 + (grp < G4 ? grp : G4 - 1)] * q_dn;     // beyond the last group: masked rows
     }
   };
+
+  // One pipeline stage, written out in issue order: the matrix instructions of tile t and, in their shadow, the
+  // epilogue of the tile before, cut into 24 slices.  (Two waves of a SIMD that each run their matrix phase and
+  // then their vector phase fall into step, and the two kinds of work then add up instead of overlapping.)
+  //   matrix part: transposed logits of the 32 x 32 tile, a[i] = <k_hat[row 8 (i/4) + 4 half + i%4 of the tile],
+  //     q_hat[i0 + n]>, as hi.hi + hi.lo + lo.hi products (lo.lo is below 2^-22 of the result) with fp32
+  //     accumulation, dealt to two accumulators c0, c1 in turn so that no matrix instruction waits for the one
+  //     before it; the operands of two product steps are requested from LDS one pair ahead; tile t + 1 goes from
+  //     its staging registers to LDS early in the stage, and only then the loads of tile t + 2 are issued, so
+  //     they have a whole stage to land.
+  //   epilogue of tile tp from its accumulators p0, p1: logits = (p0 + p1) x inverse scales (registers 4 g .. 4 g + 3
+  //     of a lane are four consecutive key rows, one scale group); one reference for the whole tile, the running
+  //     row maximum including this tile (finite from the start, so no difference is ever inf - inf; masked logits
+  //     give 2^-inf = 0; R == 8: a key block is split over the two lane halves, which therefore share the
+  //     reference); then per key block the log of its summed exponentials.
+  constexpr int NS = 3 * KS;                  // matrix instructions of a tile
+  auto stage = [&](auto do_mm, auto do_ep, int t, int buf, f32x16& c0, f32x16& c1, float (&dn_next)[4], const f32x16& p0,
+                   const f32x16& p1, const float (&dn_prev)[4], int tp) {
+    constexpr bool MM = decltype(do_mm)::value, EP = decltype(do_ep)::value;
+    const uint16_t* krow = &s_k[buf][n * RSP + 8 * half];
+    f16x8 fr[2][4];
+    auto load_pair = [&](int p) {
+      fr[p & 1][0] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 32 * p));
+      fr[p & 1][1] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 32 * p));
+      fr[p & 1][2] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + 32 * p + 16));
+      fr[p & 1][3] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(krow + D + 32 * p + 16));
+    };
+    float dp[4], c[16];
+    float mt = 0.f, m_new = 0.f, zt = 0.f;
+    if (EP) {
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) dp[gq] = dn_prev[gq];      // dn_next may be the same array
+    }
+    if (MM) {
+      load_pair(0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 0.f; }
+    }
+    auto slice = [&](int sl) {
+      if (sl < 8) {
+#pragma unroll
+        for (int i = 2 * sl; i < 2 * sl + 2; ++i) c[i] = (p0[i] + p1[i]) * dp[i / 4];
+      } else if (sl == 8) {
+        if (__builtin_expect(tp * 32 + 32 > n_live, 0)) {   // ragged end: key sub-blocks without rows count for nothing
+          asm volatile("");                   // keeps this a branch: as selects it would run on every tile
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (tp * 32 + 8 * (i / 4) + 4 * half + (i % 4) >= n_live) c[i] = -INFINITY;
+        }
+        mt = vmax3(c[0], c[1], c[2]);
+      } else if (sl < 12) {
+        const int i = 3 + 4 * (sl - 9);
+        mt = vmax3(mt, c[i], c[i + 1]);
+        mt = vmax3(mt, c[i + 2], c[i + 3]);
+      } else if (sl == 12) {
+        mt = fmaxf(mt, c[15]);
+        if (R == 8) {
+          float lo, hi;
+          both_halves(mt, lo, hi);
+          mt = fmaxf(lo, hi);
+        }
+        m_new = fmaxf(m_row, mt);
+        z_row *= __builtin_amdgcn_exp2f(m_row - m_new);
+        m_row = m_new;
+      } else {
+        if (sl < 21) {
+#pragma unroll
+          for (int i = 2 * (sl - 13); i < 2 * (sl - 13) + 2; ++i) {
+            const float e = __builtin_amdgcn_exp2f(c[i] - m_new);
+            if (G == 1) zt += e; else c[i] = e;
+          }
+        }
+        if (sl >= 20) {
+          // fold the key sub-blocks of each key block: groups of G consecutive registers
+          constexpr int NG = 16 / G;
+#pragma unroll
+          for (int gi = (sl - 20) * NG / 4; gi < (sl - 19) * NG / 4; ++gi) {
+            float tv;
+            if (G == 1) {
+              tv = c[gi];
+            } else {
+              float sg = 0.f;
+#pragma unroll
+              for (int e = 0; e < G; ++e) sg += c[gi * G + e];
+              zt += sg;                        // this lane's own share of the row sum
+              if (R == 8) {
+                float lo, hi;
+                both_halves(sg, lo, hi);
+                sg = lo + hi;
+              }
+              // a block whose sum vanishes against the row maximum (below 2^-126 of it) scores nothing: log2(0) = -inf
+              tv = m_new + __builtin_amdgcn_logf(sg);
+            }
+            // key sub-block of the group's first register: 8 (first / 4) + 4 half + first % 4
+            const int first = gi * G;
+            const int ks = tp * 32 + 8 * (first / 4) + 4 * half + (first % 4);
+            const int v = ks / R;
+            if ((R != 8 || half == 0) && v < M_v && q_row < M_s) tt_h[int64_t(v) * M_s + q_row] = tv;
+          }
+          if (sl == 23) z_row += zt;
+        }
+      }
+    };
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < NS; ++m) {
+      if (MM) {
+        const int p = m / 6, j = m % 6, kk = 2 * p;
+        if (j == 0 && p + 1 < KS / 2) load_pair(p + 1);
+        const f16x8(&f)[4] = fr[p & 1];
+        if (j == 0) c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[0], bq[0][kk], c0, 0, 0, 0);          // hi.hi
+        if (j == 1) c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[0], bq[1][kk], c1, 0, 0, 0);          // hi.lo
+        if (j == 2) c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[1], bq[0][kk], c0, 0, 0, 0);          // lo.hi
+        if (j == 3) c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[2], bq[0][kk + 1], c1, 0, 0, 0);
+        if (j == 4) c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[2], bq[1][kk + 1], c0, 0, 0, 0);
+        if (j == 5) c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[3], bq[0][kk + 1], c1, 0, 0, 0);
+        if (m == 2 && t + 1 < t_end) commit(buf ^ 1);      // the other buffer was last read before the previous barrier
+        if (m == 4 && t + 2 < t_end) fetch(t + 2);
+        if (m == NS / 2 && t + 1 < t_end) load_dn(t + 1, dn_next);   // the epilogue is done with dn_prev by now
+      }
+      if (EP) {
+#pragma unroll
+        for (int sl = m * 24 / NS; sl < (m + 1) * 24 / NS; ++sl) slice(sl);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (MM) __syncthreads();                  // tile t has been read by every wave; tile t + 1 is in LDS
+  };
+
   if (t_begin < t_end) {
-    // Tile t + 1 is written to LDS right after the matrix work of tile t, and only then the loads of tile t + 2
-    // are issued: they have a whole iteration to land, with one set of staging registers.
-    float dn_next[4];
-    load_dn(t_begin, dn_next);
+    using yes = std::true_type;
+    using no = std::false_type;
+    f32x16 xa0, xa1, ya0, ya1;                // tiles alternate between two sets of accumulators and inverse scales
+    float dx[4], dy[4];
+    load_dn(t_begin, dx);
     fetch(t_begin);
     commit(0);
     if (t_begin + 1 < t_end) fetch(t_begin + 1);
     __syncthreads();
-    for (int t = t_begin; t < t_end; ++t) {
-      const int buf = (t - t_begin) & 1;
-      float dn[4];
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) dn[gq] = dn_next[gq];
-      f32x16 c = logit_tile(buf, dn);
-      if (t + 1 < t_end) {
-        commit(buf ^ 1);                      // the other buffer was last read before the previous barrier
-        load_dn(t + 1, dn_next);
-      }
-      if (t + 2 < t_end) fetch(t + 2);
-      if (__builtin_expect(t * 32 + 32 > n_live, 0)) {   // ragged end: key sub-blocks without rows count for nothing
-        asm volatile("");                     // keeps this a branch: as selects it would run on every tile
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (t * 32 + 8 * (i / 4) + 4 * half + (i % 4) >= n_live) c[i] = -INFINITY;
-      }
-      // One reference for the whole tile: the running row maximum including this tile (finite from the start, so
-      // no difference is ever inf - inf; masked logits give 2^-inf = 0).  R == 8: a key block is split over the two
-      // lane halves, which therefore share the reference.
-      float mt = vmax3(c[0], c[1], c[2]);
-#pragma unroll
-      for (int i = 3; i < 15; i += 2) mt = vmax3(mt, c[i], c[i + 1]);
-      mt = fmaxf(mt, c[15]);
-      if (R == 8) mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-      const float m_new = fmaxf(m_row, mt);
-      z_row *= __builtin_amdgcn_exp2f(m_row - m_new);
-      m_row = m_new;
-      // fold the key sub-blocks of each key block: groups of G consecutive registers
-#pragma unroll
-      for (int gi = 0; gi < 16 / G; ++gi) {
-        float sg = 0.f;
-#pragma unroll
-        for (int e = 0; e < G; ++e) sg += __builtin_amdgcn_exp2f(c[gi * G + e] - m_new);
-        z_row += sg;                           // this lane's own share of the row sum
-        if (R == 8) sg += __shfl_xor(sg, 32, 64);
-        // a block whose sum vanishes against the row maximum (below 2^-126 of it) scores nothing: log2(0) = -inf
-        const float tv = G == 1 ? c[gi] : m_new + __builtin_amdgcn_logf(sg);
-        // key sub-block of the group's first register: 8 (first / 4) + 4 half + first % 4
-        const int first = gi * G;
-        const int ks = t * 32 + 8 * (first / 4) + 4 * half + (first % 4);
-        const int v = ks / R;
-        if ((R != 8 || half == 0) && v < M_v && q_row < M_s) tt_h[int64_t(v) * M_s + q_row] = tv;
-      }
-      __syncthreads();                        // tile t has been read by every wave; tile t + 1 is in LDS
+    int t = t_begin;
+    stage(yes{}, no{}, t, 0, xa0, xa1, dy, ya0, ya1, dy, t);
+    ++t;
+    for (; t + 1 < t_end; t += 2) {
+      stage(yes{}, yes{}, t, 1, ya0, ya1, dx, xa0, xa1, dx, t - 1);
+      stage(yes{}, yes{}, t + 1, 0, xa0, xa1, dy, ya0, ya1, dy, t);
+    }
+    if (t < t_end) {
+      stage(yes{}, yes{}, t, 1, ya0, ya1, dx, xa0, xa1, dx, t - 1);
+      stage(no{}, yes{}, t, 0, xa0, xa1, dx, ya0, ya1, dy, t);
+    } else {
+      stage(no{}, yes{}, t, 0, ya0, ya1, dy, xa0, xa1, dx, t - 1);
     }
   }
   // the two lane halves of a column hold different key blocks of the same query sub-block
@@ -413,8 +499,11 @@ static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* 
   const int groups = (s.M_s + 127) / 128, n_tiles = (n_live + 31) / 32;
   const int ksplit = choose_ksplit(int64_t(groups) * g->heads, n_tiles);
   const int per = (n_tiles + ksplit - 1) / ksplit;
-  score_lse_kernel<D, R><<<dim3(unsigned(groups * ksplit), unsigned(g->heads)), 256, 0, st>>>(q_hat, k_hat, q_down, k_down, tt, lse, s.M_s, s.M_v, n_live,
-                                                                                              per, ksplit);
+  const int wgs_per_head = groups * ksplit;
+  const int64_t total = int64_t(wgs_per_head) * g->heads;
+  const int per_xcd = int((total + 7) / 8);
+  score_lse_kernel<D, R><<<dim3(unsigned(per_xcd * 8)), 256, 0, st>>>(q_hat, k_hat, q_down, k_down, tt, lse, s.M_s, s.M_v, n_live, per, ksplit,
+                                                                      wgs_per_head, int(total), per_xcd);
   const unsigned tb = unsigned((s.M_v + 31) / 32);
   score_fold_kernel<R><<<dim3(tb, tb, unsigned(g->heads)), 256, 0, st>>>(tt, lse, score, s.M_s, s.M_v, n_live, ksplit);
 }
