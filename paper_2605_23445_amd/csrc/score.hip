@@ -151,6 +151,11 @@ __global__ void __launch_bounds__(256) pool_kernel(const void* __restrict__ q_pe
 
 // ------------------------------------------------------------------------------------ scoring
 
+// T is stored with its rows padded to whole query groups (128 sub-blocks) and its row count to whole key tiles,
+// so that the contraction kernel stores without a bounds check: [heads][t_rows][t_cols] fp32.
+__host__ __device__ inline int t_cols(int M_s) { return (M_s + 127) / 128 * 128; }
+__host__ __device__ inline int t_rows(int M_s, int R) { return (M_s + 31) / 32 * (32 / R); }
+
 constexpr float LSE_START = -1.0e30f;          // finite stand-in for "nothing seen yet" (keeps differences finite)
 
 __device__ __forceinline__ float vmax3(float a, float b, float c) {
@@ -252,7 +257,9 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
   };
   float m_row = LSE_START, z_row = 0.f;       // this lane's share of the row log-sum-exp of query sub-block i0 + n
   const int q_row = i0 + n;
-  float* tt_h = tt + int64_t(head) * M_v * M_s;
+  const int TC = t_cols(M_s);
+  float* tt_h = tt + int64_t(head) * t_rows(M_s, R) * TC;
+  const int t_lane = (R == 8 ? 0 : half) * (R == 1 ? 4 : R == 2 ? 2 : 1) * TC + q_row;   // this lane's share of a T index
   // inverse scales for the four row groups of tile t that this lane's registers cover, times the query row's
   auto load_dn = [&](int t, float (&dn)[4]) {
 #pragma unroll
@@ -355,10 +362,12 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
               tv = m_new + __builtin_amdgcn_logf(sg);
             }
             // key sub-block of the group's first register: 8 (first / 4) + 4 half + first % 4
+            // key block = (32 tp + 8 (first / 4) + first % 4) / R + the lane half's share, which is in t_lane; the
+            // uniform part goes into a scalar base.  No bounds check: T is padded, and at R = 8 both lane halves
+            // store the same value to the same place.
             const int first = gi * G;
-            const int ks = tp * 32 + 8 * (first / 4) + 4 * half + (first % 4);
-            const int v = ks / R;
-            if ((R != 8 || half == 0) && v < M_v && q_row < M_s) tt_h[int64_t(v) * M_s + q_row] = tv;
+            const int v_uniform = (tp * 32 + 8 * (first / 4) + (first % 4)) / R;
+            (tt_h + int64_t(v_uniform) * TC)[t_lane] = tv;
           }
           if (sl == 23) z_row += zt;
         }
@@ -432,7 +441,8 @@ __global__ void __launch_bounds__(256) score_fold_kernel(const float* __restrict
   __shared__ float s_t[32][33];
   const int head = blockIdx.z, u0 = blockIdx.x * 32, v0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
-  const float* tt_h = tt + int64_t(head) * M_v * M_s;
+  const int TC = t_cols(M_s);
+  const float* tt_h = tt + int64_t(head) * t_rows(M_s, R) * TC;
   const float* lse_h = lse + int64_t(head) * ksplit * M_s;
   // row log-sum-exp of the R sub-blocks of query block u0 + tx
   float l[R];
@@ -450,7 +460,7 @@ __global__ void __launch_bounds__(256) score_fold_kernel(const float* __restrict
     const int v = v0 + ty + 8 * k;
     float acc = 0.f;
     if (v < M_v && u0 + tx < M_v) {
-      const float* row = tt_h + int64_t(v) * M_s + int64_t(u0 + tx) * R;
+      const float* row = tt_h + int64_t(v) * TC + int64_t(u0 + tx) * R;
 #pragma unroll
       for (int a = 0; a < R; ++a) acc += __builtin_amdgcn_exp2f(row[a] - l[a]);
     }
@@ -466,13 +476,15 @@ __global__ void __launch_bounds__(256) score_fold_kernel(const float* __restrict
 }
 
 // Workspace: Q_hat, K_hat (two fp16 planes each, followed by the inverse scales of their row groups),
-// T [heads][M_v][M_s] fp32, row log-sum-exp [heads][KSPLIT_MAX][M_s] fp32.
+// T [heads][t_rows][t_cols] fp32 (padded, see t_cols), row log-sum-exp [heads][KSPLIT_MAX][M_s] fp32.
 constexpr int KSPLIT_MAX = 4;
 static size_t ws_planes_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_s * 2 * g->d * sizeof(uint16_t)); }
 static size_t ws_hat_bytes(const dfs_geom* g, const dfs_sizes& s) {
   return ws_planes_bytes(g, s) + align256(size_t(g->heads) * ((s.M_s + 3) / 4) * sizeof(float));
 }
-static size_t ws_tt_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * s.M_v * s.M_s * sizeof(float)); }
+static size_t ws_tt_bytes(const dfs_geom* g, const dfs_sizes& s) {
+  return align256(size_t(g->heads) * t_rows(s.M_s, s.r) * t_cols(s.M_s) * sizeof(float));
+}
 static size_t ws_lse_bytes(const dfs_geom* g, const dfs_sizes& s) { return align256(size_t(g->heads) * KSPLIT_MAX * s.M_s * sizeof(float)); }
 size_t ws_block_score(const dfs_geom* g, const dfs_sizes& s) {
   return 2 * ws_hat_bytes(g, s) + ws_tt_bytes(g, s) + ws_lse_bytes(g, s);
