@@ -134,7 +134,9 @@ int dfs_permute(const dfs_geom* g, int dtype, const void* x, const int32_t* perm
  * sub-blocks, and score[h,u,v] = sum of the r x r entries of A_hat in block pair (u,v).
  * Text blocks are not scored.  Means, softmax and sums are fp32; the logits run on the fp16 matrix cores
  * over a two-term split of the fp32 means, scaled by exact powers of two per four sub-blocks (22 bits per
- * operand: as accurate as an fp32 contraction).  Non-finite inputs give non-finite or meaningless scores.
+ * operand: as accurate as an fp32 contraction; an element more than 2^14 times smaller than the largest of its
+ * four sub-blocks is kept to 2^-36 of that largest one instead).  Non-finite inputs give non-finite or
+ * meaningless scores.
  *   q_perm, k_perm [heads, N_pad, d] in (`dtype`);  score [heads, M_v, M_v] out, fp32.
  * ws: DFS_WS_BLOCK_SCORE (the pooled means and an fp32 array of about heads x M_v x M_s partial log-sums,
  * padded to whole tiles: 0.33 GB at 75 600 tokens x 40 heads).

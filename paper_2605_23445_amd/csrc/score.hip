@@ -41,7 +41,8 @@ __device__ __forceinline__ void split2(float x, uint16_t& hi, uint16_t& lo) {
 }
 // Rows are scaled in groups of four consecutive sub-blocks (the four waves of a pooling work-group) by a power of
 // two that brings the group's largest magnitude into [2^11, 2^12); `down` is the inverse.  Powers of two: exact.
-constexpr int SHIFT_MAX = 100;                 // keeps both factors finite for groups of vanishing magnitude
+constexpr int SHIFT_MAX = 126;                 // keeps both factors finite and normal for groups of vanishing magnitude
+                                               // (the largest finite fp32 needs a shift of -116)
 __device__ __forceinline__ void group_scale(float gmax, float& up, float& down) {
   up = 1.0f; down = 1.0f;
   if (gmax > 0.f && gmax < INFINITY) {

@@ -141,6 +141,34 @@ def test_score_and_select_small(w):
     assert np.array_equal(st.kv_cnt.cpu().numpy()[:, :sz["M_v"]], k_row_o + sz["M_x"])
 
 
+@pytest.mark.parametrize("w", [MID_BF16, MID_D64, MID_F32], ids=lambda w: w.name)
+def test_score_is_unchanged_by_exact_rescalings(w):
+    """The contraction scales its operands by powers of two and undoes it on the result.  Rescalings of the inputs
+    that leave every logit unchanged (Q x 2^-30 with K x 2^30; a subset of the features of Q x 2^-6 with the same
+    features of K x 2^6) must give scores within the tolerance of the oracle on the rescaled inputs, and the
+    oracle's scores themselves are the same as without rescaling."""
+    from workloads.synth import to_bf16_bits
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v, perm_pad_o, _, _ = _oracle_inputs(w)
+    perm_pad, _, _ = G.gpu_perm(g)
+    want0 = O.block_score(O.permute(as_f64(q), perm_pad_o), O.permute(as_f64(k), perm_pad_o), sz["N_v"], w.B, w.Bs)
+    feat = np.ones(w.d); feat[::3] = 2.0 ** 6
+    for fq, fk in ((2.0 ** -30, 2.0 ** 30), (1.0 / feat, feat)):
+        q64, k64 = as_f64(q) * fq, as_f64(k) * fk                     # powers of two: exact in bf16 and fp32
+        if w.dtype == "bf16":
+            q2, k2 = to_bf16_bits(q64.astype(np.float32)), to_bf16_bits(k64.astype(np.float32))
+        else:
+            q2, k2 = q64.astype(np.float32), k64.astype(np.float32)
+        assert np.array_equal(as_f64(q2), q64) and np.array_equal(as_f64(k2), k64)
+        want = O.block_score(O.permute(q64, perm_pad_o), O.permute(k64, perm_pad_o), sz["N_v"], w.B, w.Bs)
+        assert np.abs(want - want0).max() <= 1e-12
+        qp, kp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q2, k2))
+        err = np.abs(G.gpu_score(g, dt, qp, kp).cpu().numpy() - want).max()
+        say(f"  {w.name}: score max err {err:.3e} under rescaling")
+        assert err <= SCORE_TOL * sz["r"]
+
+
 @pytest.mark.parametrize("T,H,W,Bs", [(4, 48, 48, 32), (6, 32, 64, 32), (5, 40, 50, 16)])
 def test_score_key_range_splits(T, H, W, Bs):
     """Scoring on shapes where one head's work is split over three and four key ranges per query group
