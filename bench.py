@@ -70,6 +70,9 @@ def parse():
     ap.add_argument("--sparsity", type=float, default=None, help="target block sparsity (default 0.9; the workload's cap for a caching schedule)")
     ap.add_argument("--keep-all", action="store_true", help="keep every key block: the same kernels as a dense attention (in-house dense time)")
     ap.add_argument("--heads", type=int, default=0, help="override the head count (debugging)")
+    ap.add_argument("--sub-block", type=int, default=0, metavar="BS",
+                    help="override the sub-block size B_s of the scoring stage (the benchmark configurations use 32; the paper's "
+                         "own default is 16, Sec. 6.1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="instead of the benchmark: measure what the chip sustains on bare matrix-instruction chains and on a "
@@ -106,6 +109,9 @@ def main():
     w = CONFIGS[a.workload]
     if a.heads:
         w = w.with_heads(a.heads)
+    if a.sub_block:
+        from dataclasses import replace
+        w = replace(w, Bs=a.sub_block)
     schedule = w.mass > 0.0          # the workload with a mask-caching schedule
     if a.steps is None:
         a.steps = w.steps if schedule else 10
@@ -320,6 +326,9 @@ def paper_schedule_bench(a, P):
     w = CONFIGS["wan"]
     if a.heads:
         w = w.with_heads(a.heads)
+    if a.sub_block:
+        from dataclasses import replace
+        w = replace(w, Bs=a.sub_block)
     total_steps = a.steps if a.steps else 50
     delta = 12
     sz = derived_sizes(w)
