@@ -21,10 +21,7 @@
 namespace dfs {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // ------------------------------------------------------------------------------------ pooling
@@ -196,7 +193,7 @@ __device__ __forceinline__ void lse_merge(float& m, float& z, float m2, float z2
 template <int D, int R>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict__ k_hat, const float* __restrict__ q_down,
-                 const float* __restrict__ k_down, float* __restrict__ tt, float* __restrict__ lse, int M_s, int M_v, int n_live, int tiles_per_split, int ksplit,
+                 const float* __restrict__ k_down, float* __restrict__ tt, float* __restrict__ lse, int M_s, int n_live, int tiles_per_split, int ksplit,
                  int wgs_per_head, int total_wgs, int wgs_per_xcd) {
   constexpr int RS = 2 * D;                   // elements of a centroid row (hi, lo planes)
   constexpr int RSP = RS + 8;                 // LDS row stride: 16 bytes of skew keep the row-per-lane reads conflict-free
@@ -403,8 +400,11 @@ score_lse_kernel(const uint16_t* __restrict__ q_hat, const uint16_t* __restrict_
   if (t_begin < t_end) {
     using yes = std::true_type;
     using no = std::false_type;
-    f32x16 xa0, xa1, ya0, ya1;                // tiles alternate between two sets of accumulators and inverse scales
-    float dx[4], dy[4];
+    // tiles alternate between two sets of accumulators and inverse scales (the second set is handed, unused, to the
+    // first stage, which has no epilogue)
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 xa0 = zero16, xa1 = zero16, ya0 = zero16, ya1 = zero16;
+    float dx[4] = {1.f, 1.f, 1.f, 1.f}, dy[4] = {1.f, 1.f, 1.f, 1.f};
     load_dn(t_begin, dx);
     fetch(t_begin);
     commit(0);
@@ -515,7 +515,7 @@ static void launch_score(const dfs_geom* g, const dfs_sizes& s, const uint16_t* 
   const int wgs_per_head = groups * ksplit;
   const int64_t total = int64_t(wgs_per_head) * g->heads;
   const int per_xcd = int((total + 7) / 8);
-  score_lse_kernel<D, R><<<dim3(unsigned(per_xcd * 8)), 256, 0, st>>>(q_hat, k_hat, q_down, k_down, tt, lse, s.M_s, s.M_v, n_live, per, ksplit,
+  score_lse_kernel<D, R><<<dim3(unsigned(per_xcd * 8)), 256, 0, st>>>(q_hat, k_hat, q_down, k_down, tt, lse, s.M_s, n_live, per, ksplit,
                                                                       wgs_per_head, int(total), per_xcd);
   const unsigned tb = unsigned((s.M_v + 31) / 32);
   score_fold_kernel<R><<<dim3(tb, tb, unsigned(g->heads)), 256, 0, st>>>(tt, lse, score, s.M_s, s.M_v, n_live, ksplit);
