@@ -289,9 +289,9 @@ def main():
                            "permute_frac_of_measured_copy": bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9 / MEASURED_COPY_GBS,
                            "source": "profiles/mi355x_sustained_rates.txt (bench.py --probe)"},
         "binding_bound": ("attention: bf16 matrix cores, rated against their peak; on key lists without locality (the synthetic "
-                          "benchmark's) the kernel also pulls about twenty times its compulsory bytes from beyond L2, at the rate "
-                          "the chip's copy kernels reach (traffic / launch time against row_gather_gbs), which then limits it "
-                          "first (at d = 64 the vector work per matrix instruction doubles and vector issue limits it); "
+                          "benchmark's) the kernel also pulls about twenty times its compulsory bytes from beyond L2 "
+                          "(attn_beyond_l2_gbs: three quarters of what a read-only probe reaches), and that traffic, not the "
+                          "softmax, then limits it first (at d = 64 the vector work per matrix instruction doubles and vector issue limits it); "
                           "permute: HBM; scoring: pooling at the copy rate, then the issue rate of its fp32-accurate contraction"),
         "attn_beyond_l2_gbs": None if traffic is None else traffic / (attn_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if w.dtype == "bf16" else "attn_f32_kernel",
