@@ -505,7 +505,8 @@ def ablation(a, P):
 
 
 def probe_rates(P, torch):
-    """Sustained rates of the chip: matrix-instruction chains at one and two waves per SIMD, and a 1 GiB copy."""
+    """Sustained rates of the chip: matrix-instruction chains at one and two waves per SIMD, a 1 GiB copy, and
+    read-only traffic in random 64 KB pieces."""
     torch.cuda.set_device(0)
     out = {"probe": "MI355X sustained rates", "nominal": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS}}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -533,6 +534,20 @@ def probe_rates(P, torch):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / 5
     out["copy_1GiB"] = {"gbs_read_plus_write": 2.0 * (1 << 30) / ms * 1e-6, "ms": ms}
+    del dst
+    # read-only traffic in 64 KB pieces at random places, as the attention kernel's tile loads: from a region the 4 MB L2s
+    # hold, one the memory-side cache holds, and HBM
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    wgs, per_wg = 4096, 64
+    out["read_random_64KB_pieces"] = {}
+    for mib in (8, 40, 160, 1024):
+        region = src[: mib << 20]
+        P.dfs_probe_read(region, wgs, per_wg, sink)
+        torch.cuda.synchronize()
+        e0.record(); P.dfs_probe_read(region, wgs, per_wg, sink); e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        out["read_random_64KB_pieces"][f"region_{mib}_MiB"] = {"gbs_requested": wgs * per_wg * 65536.0 / ms * 1e-6, "ms": ms}
     print(json.dumps(out))
 
 

@@ -292,10 +292,14 @@ int dfs_attn_clock_probe(uint64_t* counters);
  * (32768 flop each per wave) and nothing else; sink [work_groups * 256] fp32 out (device);
  * counters (device, 2 x uint64, zeroed by the caller, or NULL) receives work-group 0's shader-clock cycles and
  * 100 MHz ticks.  dfs_probe_copy copies `bytes` (a multiple of 16, 16-byte aligned device pointers) with
- * 16 bytes per lane.  Time them with events on `stream`.
+ * 16 bytes per lane.  dfs_probe_read launches `work_groups` x 256 threads that each read `pieces_per_wg`
+ * 64 KB pieces of the region src[0, bytes) (a multiple of 64 KB, 16-byte aligned) at seeded pseudo-random piece
+ * indices and nothing else: read-only traffic of the shape of the attention kernel's tile loads; sink (device,
+ * one uint32) is written only for one particular checksum.  Time them with events on `stream`.
  */
 int dfs_probe_mfma(int32_t work_groups, int32_t iters, float* sink, uint64_t* counters, void* stream);
 int dfs_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int dfs_probe_read(const void* src, size_t bytes, int32_t work_groups, int32_t pieces_per_wg, uint32_t* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -79,6 +79,7 @@ def _load():
         "dfs_attn_clock_probe": (C.c_int, [vp]),
         "dfs_probe_mfma": (C.c_int, [i32, i32, vp, vp, vp]),
         "dfs_probe_copy": (C.c_int, [vp, vp, sz, vp]),
+        "dfs_probe_read": (C.c_int, [vp, sz, C.c_int32, C.c_int32, vp, vp]),
         "dfs_forward": (C.c_int, [gp, C.c_int, vp, vp, vp, vp, vp, C.c_int, C.c_int, dbl, dbl,
                                   C.POINTER(_MaskStateC), f32, vp, vp, sz, vp]),
     }
@@ -91,7 +92,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("dfs_geom_sizes", "dfs_workspace_bytes", "dfs_last_error", "dfs_keep_count", "dfs_hilbert_perm", "dfs_permute",
            "dfs_block_score", "dfs_select_mask", "dfs_sparse_attn_fwd", "dfs_unperm", "dfs_forward", "dfs_token_order", "dfs_recall",
-           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused", "dfs_probe_mfma", "dfs_probe_copy",
+           "dfs_schedule", "dfs_block_score_src", "dfs_sparse_attn_fwd_src", "dfs_attn_clock_probe", "dfs_block_score_fused", "dfs_probe_mfma", "dfs_probe_copy", "dfs_probe_read",
            "dfs_select_mask_static")
 DFS_ORDER_HILBERT3D, DFS_ORDER_RASTER, DFS_ORDER_HILBERT2D, DFS_ORDER_BLOCK3D = 0, 1, 2, 3
 
@@ -276,6 +277,12 @@ def dfs_probe_copy(src: torch.Tensor, dst: torch.Tensor):
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     _check(_lib.dfs_probe_copy(_ptr(src), _ptr(dst), n, _stream()))
+
+
+def dfs_probe_read(src: torch.Tensor, work_groups: int, pieces_per_wg: int, sink: torch.Tensor):
+    """Measurement probe: read-only traffic, random 64 KB pieces of `src` (size a multiple of 64 KB)."""
+    n = src.numel() * src.element_size()
+    _check(_lib.dfs_probe_read(_ptr(src), n, int(work_groups), int(pieces_per_wg), _ptr(sink, torch.int32, 1, "sink"), _stream()))
 
 
 def dfs_unperm(g: Geom, dtype: int, o_perm, inv, o):

@@ -39,6 +39,25 @@ __global__ void __launch_bounds__(256) copy_kernel(const u32x4* __restrict__ src
   for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += size_t(gridDim.x) * 256) dst[i] = src[i];
 }
 
+// Read-only traffic of the shape the attention kernel's tile loads have: every work-group reads `pieces_per_wg` 64 KB
+// pieces of the region at seeded pseudo-random piece indices (non-temporal 16-byte loads) and does nothing else.
+// The checksum keeps the loads alive; sink[0] is written only if it takes one particular value.
+__global__ void __launch_bounds__(256) read_pieces_kernel(const u32x4* __restrict__ src, unsigned long long pieces, int pieces_per_wg,
+                                                          unsigned int* __restrict__ sink) {
+  unsigned int acc = 0, seed = blockIdx.x * 2654435761u + 12345u;
+  for (int i = 0; i < pieces_per_wg; ++i) {
+    seed = seed * 1664525u + 1013904223u;
+    const unsigned long long piece = ((unsigned long long)(seed >> 8) * pieces) >> 24;   // < pieces
+    const u32x4* p = src + piece * 4096;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {                                                          // 256 threads x 16 B x 16
+      const u32x4 v = __builtin_nontemporal_load(p + j * 256 + threadIdx.x);
+      acc += v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+  }
+  if (acc == 0x12345678u) sink[0] = acc;
+}
+
 }  // namespace dfs
 
 using namespace dfs;
@@ -56,4 +75,14 @@ extern "C" int dfs_probe_copy(const void* src, void* dst, size_t bytes, void* st
   if (bytes % 16 || misaligned(16, {src, dst})) return fail(DFS_EINVAL, "dfs_probe_copy: pointers and size must be multiples of 16 bytes");
   copy_kernel<<<8192, 256, 0, as_stream(stream)>>>(static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), bytes / 16);
   return launch_status("dfs_probe_copy");
+}
+
+extern "C" int dfs_probe_read(const void* src, size_t bytes, int32_t work_groups, int32_t pieces_per_wg, uint32_t* sink, void* stream) {
+  if (!src || !sink) return fail(DFS_EINVAL, "dfs_probe_read: NULL argument");
+  if (bytes < 65536 || bytes % 65536 || misaligned(16, {src}) || misaligned(4, {sink}))
+    return fail(DFS_EINVAL, "dfs_probe_read: the region must be a multiple of 64 KB and 16-byte aligned, sink 4-byte aligned");
+  if (work_groups < 1 || work_groups > 65535 || pieces_per_wg < 1) return fail(DFS_EINVAL, "dfs_probe_read: need 1 <= work_groups <= 65535 and pieces_per_wg >= 1");
+  if (bytes / 65536 > (1ull << 24)) return fail(DFS_EINVAL, "dfs_probe_read: region above 1 TiB");
+  read_pieces_kernel<<<unsigned(work_groups), 256, 0, as_stream(stream)>>>(static_cast<const u32x4*>(src), bytes / 65536, pieces_per_wg, sink);
+  return launch_status("dfs_probe_read");
 }

@@ -141,7 +141,7 @@ def test_attention_clock_probe_counts_every_work_group():
 
 
 def test_measurement_probes_run_and_report_sane_rates():
-    """The two probes behind `bench.py --probe`: a short matrix-instruction chain and a copy."""
+    """The probes behind `bench.py --probe`: a short matrix-instruction chain, a copy and a read-only pass."""
     sink = torch.empty(64 * 256, dtype=torch.float32, device="cuda")
     counters = torch.zeros(2, dtype=torch.int64, device="cuda")
     P.dfs_probe_mfma(64, 2000, sink, counters)
@@ -157,6 +157,13 @@ def test_measurement_probes_run_and_report_sane_rates():
     assert torch.equal(src, dst)
     with pytest.raises(P.DfsError):
         P.dfs_probe_mfma(0, 10, sink, None)
+    region = torch.ones(4 << 20, dtype=torch.uint8, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    P.dfs_probe_read(region, 64, 8, flag)
+    torch.cuda.synchronize()
+    assert int(flag) == 0                                                     # all-ones words cancel in the checksum
+    with pytest.raises(P.DfsError):
+        P.dfs_probe_read(region[:1000], 64, 8, flag)                          # not a multiple of 64 KB
 
 
 def test_whole_step_under_graph_capture_replays_bit_identical():
