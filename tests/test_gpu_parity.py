@@ -548,6 +548,56 @@ def test_full_size_caching_schedule():
             assert worst <= BF16_MAX and total / count <= BF16_MEAN
 
 
+DMG_F32 = Workload("dmg_f32", 4, 10, 16, heads=2, d=64, dtype="f32", B=64, Bs=16, sparsity=(0.5,), seed=81)   # 640 tokens, 10 blocks
+
+
+@pytest.mark.parametrize("w", [MID_BF16, MID_D64, DMG_F32], ids=lambda w: w.name)
+def test_damaged_lists_and_orders_stay_in_bounds(w):
+    """Lists and orders that break the documented format are turned into defined behaviour by the kernels' own
+    checks (a count below zero keeps nothing, a count above K_max is cut to K_max, a block id outside [0, M) reads
+    block 0, an order entry outside [0, N) is a pad): the launches complete, every query block with an intact list
+    gives bit for bit what it gives in the clean run, and nothing non-finite appears."""
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v, perm_pad_o, inv_o, blk_valid = _oracle_inputs(w)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    qp, kp, vp = (G.gpu_permute(g, dt, G.to_dev(x), perm_pad) for x in (q, k, v))
+    st = G.gpu_select(g, G.gpu_score(g, dt, qp, kp), P.DFS_SELECT_TOPK, w.sparsity[0], K_max=sz["M"])
+    o_ref, lse_ref = G.gpu_attn(g, dt, qp, kp, vp, st)
+    bad = P.MaskState(st.kv_idx.clone(), st.kv_cnt.clone(), None, None, st.K_max)
+    bad.kv_cnt[0, 1] = -5                                    # keeps nothing
+    bad.kv_cnt[0, 2] = st.K_max + 7 if st.K_max + 7 < sz["M"] else sz["M"] - 1   # cut to K_max; the tail of the row is junk
+    bad.kv_idx[0, 2, int(st.kv_cnt[0, 2]):] = torch.tensor([-1, sz["M"] + 3, 2 ** 30][: 1], dtype=torch.int32, device="cuda")
+    bad.kv_idx[0, 3, 0] = sz["M"] + 5                        # one id out of range: block 0 instead
+    bad.kv_idx[1, 0, 0] = -7
+    o_bad, lse_bad = G.gpu_attn(g, dt, qp, kp, vp, bad)
+    torch.cuda.synchronize()
+    B = w.B
+    assert bool(torch.isfinite(o_bad.float()).all())
+    assert bool((o_bad[0, B:2 * B] == 0).all()) and bool(torch.isneginf(lse_bad[0, B:2 * B]).all())
+    intact = torch.ones((w.heads, sz["M"]), dtype=torch.bool)
+    intact[0, 1] = intact[0, 2] = intact[0, 3] = intact[1, 0] = False
+    rows = intact.repeat_interleave(B, dim=1).cuda()
+    assert torch.equal(o_bad[rows], o_ref[rows]) and torch.equal(lse_bad[rows], lse_ref[rows])
+    # a damaged order: entries beyond N and below -1 are pads for the gather, and are skipped by the scatter
+    perm_bad = perm_pad.clone()
+    perm_bad[5] = sz["N"] + 11
+    perm_bad[6] = -4
+    x = G.to_dev(q)
+    got = G.gpu_permute(g, dt, x, perm_bad)
+    want = G.gpu_permute(g, dt, x, perm_pad)
+    assert bool((got[:, 5] == 0).all()) and bool((got[:, 6] == 0).all())
+    keep = torch.ones(sz["N_pad"], dtype=torch.bool, device="cuda"); keep[5] = keep[6] = False
+    assert torch.equal(got[:, keep], want[:, keep])
+    inv_bad = inv.clone()
+    inv_bad[9] = sz["N_pad"] + 100
+    inv_bad[10] = -3
+    back = G.gpu_unperm(g, dt, want, inv_bad)
+    torch.cuda.synchronize()
+    keep_n = torch.ones(sz["N"], dtype=torch.bool, device="cuda"); keep_n[9] = keep_n[10] = False
+    assert torch.equal(back[:, keep_n], x[:, keep_n])
+
+
 @pytest.mark.parametrize("w", [MID_BF16, MID_D64, MID_B64], ids=lambda w: w.name)
 def test_source_order_variants_are_bit_identical(w):
     """dfs_block_score_src / dfs_sparse_attn_fwd_src (Q gathered, O scattered through the permutation) give the
