@@ -201,6 +201,8 @@ int dfs_select_mask_static(const dfs_geom* g, const float* score, int mode, doub
  *       lse is requested the bf16 kernel keeps the unrounded fp32 sum beside it, at a few per cent of its
  *       speed, because ln of the rounded sum would be off by up to bf16's unit roundoff 2^-8.)
  *   scale: softmax scale, 1/sqrt(d) in the paper.
+ * Lists that break the format cannot make the kernels read out of bounds: a count below zero keeps nothing, a
+ * count above K_max (and below M) is cut to K_max, a block id outside [0, M) is read as block 0.
  */
 int dfs_sparse_attn_fwd(const dfs_geom* g, int dtype, const void* q_perm, const void* k_perm,
                         const void* v_perm, const int32_t* kv_idx, const int32_t* kv_cnt, int32_t K_max,
