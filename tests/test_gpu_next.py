@@ -220,3 +220,41 @@ def test_whole_step_under_graph_capture_replays_bit_identical():
             assert torch.equal(eager.st.k_head, cap.st.k_head) or mode == P.DFS_SELECT_TOPK
             assert torch.equal(eager.o, eager.o1), "one-call entry point and staged calls differ"
             assert bool(torch.isfinite(cap.o.float()).all())
+
+
+def test_two_streams_share_no_hidden_state():
+    """Two one-call forwards on two streams at the same time, each with its own inputs, mask state, workspace and
+    output: each must give bit for bit what it gives alone (the library keeps no state between calls besides what the
+    caller passes in)."""
+    w = Workload("streams_mid", 5, 12, 20, heads=3, d=128, dtype="bf16", B=128, Bs=32, sparsity=(0.6,), seed=91)
+    sz = derived_sizes(w)
+    g, dt = G.geom_of(w), G.dtype_of(w)
+    q, k, v = make_qkv(w)
+    perm_pad, inv, _ = G.gpu_perm(g)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    K_max, scale = sz["M"], 1 / math.sqrt(w.d)
+
+    class Job:
+        def __init__(self, shift):
+            self.q, self.k, self.v = (torch.roll(G.to_dev(x), shift, dims=1).contiguous() for x in (q, k, v))
+            self.st = P.MaskState(torch.zeros((w.heads, sz["M"], K_max), **i32), torch.zeros((w.heads, sz["M"]), **i32),
+                                  torch.zeros((w.heads, sz["M"], sz["M"]), dtype=torch.uint8, device="cuda"), None, K_max)
+            self.ws = G.ws_tensor(P.dfs_workspace_bytes(g, P.DFS_WS_FORWARD_BF16))
+            self.o = torch.zeros_like(self.q)
+
+        def run(self, sparsity):
+            P.dfs_forward(g, dt, self.q, self.k, self.v, perm_pad, inv, True, P.DFS_SELECT_TOPK, sparsity, 0.0, self.st, scale, self.o, self.ws)
+
+    alone = [Job(0), Job(37)]
+    alone[0].run(0.6); alone[1].run(0.8)
+    torch.cuda.synchronize()
+    both = [Job(0), Job(37)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for job, stream, sp in zip(both, streams, (0.6, 0.8)):
+            with torch.cuda.stream(stream):
+                job.run(sp)
+    torch.cuda.synchronize()
+    for a, b in zip(alone, both):
+        assert torch.equal(a.o, b.o) and torch.equal(a.st.kv_cnt, b.st.kv_cnt) and torch.equal(a.st.mask, b.st.mask)
